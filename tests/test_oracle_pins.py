@@ -1,0 +1,319 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Each test names the passage or the mathematical fact it holds the oracle to.
+"""
+import itertools
+import math
+import os
+import subprocess
+import sys
+from collections import Counter, deque
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import oracle
+from helpers import check_mfg, csr_from_adj, random_simple_graph
+
+
+# ---------------------------------------------------------------------------------------------
+# Philox4x32-10 against an independent library implementation (PyTorch's header-only engine)
+# ---------------------------------------------------------------------------------------------
+
+_DRIVER = r"""
+#include <ATen/core/PhiloxRNGEngine.h>
+#include <cstdio>
+#include <cstdlib>
+int main(int argc, char** argv) {
+  // argv: seed offset subsequence  -> prints the next 4 words
+  for (int a = 1; a + 2 < argc; a += 3) {
+    unsigned long long seed = strtoull(argv[a], 0, 0), off = strtoull(argv[a+1], 0, 0),
+                       sub = strtoull(argv[a+2], 0, 0);
+    at::philox_engine e(seed, sub, 0);
+    e.set_offset(off);
+    unsigned w0 = e(), w1 = e(), w2 = e(), w3 = e();
+    printf("%u %u %u %u\n", w0, w1, w2, w3);
+  }
+  return 0;
+}
+"""
+
+
+@pytest.fixture(scope="module")
+def torch_philox(tmp_path_factory):
+    import torch
+    inc = os.path.join(os.path.dirname(torch.__file__), "include")
+    if not os.path.exists(os.path.join(inc, "ATen/core/PhiloxRNGEngine.h")):
+        pytest.skip("PyTorch Philox header not shipped")
+    d = tmp_path_factory.mktemp("philox")
+    src, exe = d / "drv.cpp", d / "drv"
+    src.write_text(_DRIVER)
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-I", inc, str(src), "-o", str(exe)])
+
+    def run(cases):
+        args = [str(x) for c in cases for x in c]
+        out = subprocess.check_output([str(exe)] + args, text=True)
+        return [[int(t) for t in line.split()] for line in out.strip().splitlines()]
+    return run
+
+
+def test_philox_matches_library_engine(torch_philox):
+    """Section 4.1 names no generator; the reading is Philox4x32-10 (Salmon et al., SC'11).
+    The library engine uses key = (seed lo, seed hi), counter = (offset lo, offset hi,
+    subsequence lo, subsequence hi)."""
+    rng = np.random.default_rng(7)
+    cases = [(0, 0, 0), (1, 0, 0), (0, 1, 0), (0, 0, 1), (2**64 - 1, 2**64 - 1, 2**64 - 1)]
+    cases += [tuple(int(x) for x in rng.integers(0, 2**63, size=3) * 2 + rng.integers(0, 2, size=3))
+              for _ in range(40)]
+    got = torch_philox(cases)
+    for (seed, off, sub), words in zip(cases, got):
+        ctr = [off & 0xFFFFFFFF, off >> 32, sub & 0xFFFFFFFF, sub >> 32]
+        key = [seed & 0xFFFFFFFF, seed >> 32]
+        assert oracle.philox4x32_10(ctr, key) == words, (seed, off, sub)
+
+
+def test_draw_word_layout(torch_philox):
+    """Reading: the s-th word of (rng_key, hop h, dst v) is word s%4 of the block with
+    counter (v, h, s/4, 0) and key (rng_key lo, rng_key hi).  Checked through
+    sample_positions on a row long enough that position == floor(word * m / 2^32) can be
+    inverted: deg = 2^31, fanout 1 gives p[0] = floor(word * 2^31 / 2^32) = word >> 1."""
+    for key, v, h in [(0x0123456789ABCDEF, 12345, 2), (99, 0, 0), (2**64 - 1, 2**31 - 1, 5)]:
+        words = torch_philox([(key, v | (h << 32), 0)])[0]
+        p = oracle.sample_positions(2**31, 1, key, v, h)
+        assert p == [words[0] >> 1]
+    # words 0..7 of one destination: fanout 8 on a huge row; with deg = 2^31 + 7 - s the
+    # collision branch is practically unreachable, so p[s] = floor(w_s * (deg-8+s+1) / 2^32)
+    key, v, h = 0xDEADBEEF12345678, 777, 1
+    blocks = torch_philox([(key, v | (h << 32), 0), (key, v | (h << 32), 1)])
+    w = blocks[0] + blocks[1]
+    deg = 2**31
+    p = oracle.sample_positions(deg, 8, key, v, h)
+    assert p == [(w[s] * (deg - 8 + s + 1)) >> 32 for s in range(8)]
+
+
+# ---------------------------------------------------------------------------------------------
+# Floyd's subset algorithm is exactly uniform given ideal indices (brute force)
+# ---------------------------------------------------------------------------------------------
+
+def _word_for(t, m):
+    """Smallest 32-bit word r with floor(r * m / 2^32) == t."""
+    r = -(-(t << 32) // m)
+    assert (r * m) >> 32 == t and r < 2**32
+    return r
+
+
+@pytest.mark.parametrize("n,k", [(4, 2), (5, 3), (6, 1), (6, 4), (7, 3), (5, 5)])
+def test_floyd_exhaustive_uniform(n, k):
+    """Enumerating every tuple of ideal indices (t_s uniform on [0, n-k+s]) must produce each
+    k-subset of [0, n) exactly k! times, and never a repeated position ("sampled without
+    replacement", section 2.2)."""
+    ranges = [range(n - k + s + 1) for s in range(k)]
+    seen = Counter()
+    for ts in itertools.product(*ranges):
+        words = [_word_for(t, n - k + s + 1) for s, t in enumerate(ts)]
+        p = oracle.floyd_positions(n, k, words)
+        assert len(p) == k and len(set(p)) == k and all(0 <= x < n for x in p)
+        seen[frozenset(p)] += 1
+    assert len(seen) == math.comb(n, k)
+    assert set(seen.values()) == {math.factorial(k)}
+
+
+def test_index_from_word_is_floor_scaling():
+    """floor(r * m / 2^32) at the interval edges, against big-int arithmetic."""
+    for m in [1, 2, 3, 7, 1000, 2**31, 2**32 - 1]:
+        for r in [0, 1, 2**31 - 1, 2**31, 2**32 - 1, min(2**32 - 1, (2**32) // m),
+                      max(0, (2**32) // m - 1)]:
+            assert oracle.floyd_positions(m, 1, [r]) == [(r * m) >> 32]
+
+
+# ---------------------------------------------------------------------------------------------
+# structural invariants by brute force on small graphs
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+@pytest.mark.parametrize("fanouts", [(3,), (4, 2), (2, 3, 2), (1, 1, 1, 1)])
+def test_invariants_small_graphs(seed, fanouts):
+    rng = np.random.default_rng(seed)
+    adj = random_simple_graph(60, 5, rng, hub=30)
+    indptr, indices = csr_from_adj(adj)
+    feat = rng.standard_normal((60, 6)).astype(np.float32)
+    orc = oracle.Oracle(indptr, indices, feat)
+    seeds = rng.choice(60, size=7, replace=False).astype(np.int32)
+    r = orc.sample_mfg(seeds, fanouts, rng_key=1000 + seed)
+    assert r.status == 0
+    check_mfg(indptr, indices, seeds, fanouts, r.node_ids, r.indptr, r.indices,
+              r.num_nodes, r.num_edges)
+    # Listing 1: xs = x[ids], byte for byte
+    assert np.array_equal(r.features, feat[r.node_ids].view(np.uint8).reshape(len(r.node_ids), -1))
+    assert (orc.local_of == -1).all()
+
+
+def _bfs_mfg(adj, seeds, L):
+    """Textbook reference for the RNG-free case: when every fanout >= max degree, hop h lists
+    the full neighbourhood of every known node, new nodes numbered in discovery order."""
+    order = list(seeds)
+    local = {v: i for i, v in enumerate(order)}
+    blocks, sizes = [], [len(order)]
+    for _ in range(L):
+        n_dst = len(order)
+        bp, bi = [0], []
+        for i in range(n_dst):
+            for u in adj[order[i]]:
+                if u not in local:
+                    local[u] = len(order)
+                    order.append(u)
+                bi.append(local[u])
+            bp.append(len(bi))
+        blocks.append((bp, bi))
+        sizes.append(len(order))
+    return order, blocks, sizes
+
+
+@pytest.mark.parametrize("L", [1, 2, 3])
+def test_full_neighbourhood_equals_bfs(L):
+    """All fanouts >= max degree: no random draw, the result is the L-hop neighbourhood in
+    discovery order ("at most d neighbours", section 2.2; "repeated for each source node",
+    section 4.1; dst nodes first then first-encounter order, OneHopMFG)."""
+    rng = np.random.default_rng(11)
+    adj = random_simple_graph(200, 4, rng)
+    maxdeg = max(len(r) for r in adj)
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    seeds = [5, 17, 3, 150]
+    for key in (1, 2):      # the key must not matter
+        r = orc.sample_mfg(np.array(seeds, dtype=np.int32), [maxdeg] * L, rng_key=key)
+        order, blocks, sizes = _bfs_mfg(adj, seeds, L)
+        assert r.num_nodes == sizes
+        assert r.node_ids.tolist() == order
+        for h in range(L):
+            assert r.indptr[h].tolist() == blocks[h][0]
+            assert r.indices[h].tolist() == blocks[h][1]
+    # and the set of nodes is the textbook BFS ball of radius L
+    dist = {s: 0 for s in seeds}
+    q = deque(seeds)
+    while q:
+        v = q.popleft()
+        if dist[v] == L:
+            continue
+        for u in adj[v]:
+            if u not in dist:
+                dist[u] = dist[v] + 1
+                q.append(u)
+    assert set(r.node_ids.tolist()) == set(dist)
+
+
+def test_consumer_contract_prefix_and_last_block():
+    """Appendix C model listings: dst nodes are a prefix of the src nodes (x_target = x[:size[1]])
+    and the block consumed last has the batch size as its dst count."""
+    rng = np.random.default_rng(5)
+    adj = random_simple_graph(300, 8, rng)
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    seeds = rng.choice(300, size=16, replace=False).astype(np.int32)
+    r1 = orc.sample_mfg(seeds, (3, 2), 42)
+    r2 = orc.sample_mfg(seeds, (3,), 42)
+    assert len(r1.indptr[0]) - 1 == 16
+    # hop 0 of a deeper MFG equals the 1-hop MFG (nodes of hop h never depend on later hops)
+    assert np.array_equal(r1.indices[0], r2.indices[0])
+    assert np.array_equal(r1.node_ids[:len(r2.node_ids)], r2.node_ids)
+
+
+# ---------------------------------------------------------------------------------------------
+# determinism / keying
+# ---------------------------------------------------------------------------------------------
+
+def test_keying_properties():
+    """The sample of (rng_key, hop, node) is a pure function of those three: it does not depend
+    on the batch the node sits in, nor on its position; changing any of the three changes it."""
+    rng = np.random.default_rng(3)
+    adj = random_simple_graph(400, 30, rng)
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    a = np.array([10, 20, 30, 40], dtype=np.int32)
+    b = np.array([40, 7, 10], dtype=np.int32)
+    ra, rb = orc.sample_mfg(a, (5,), 77), orc.sample_mfg(b, (5,), 77)
+
+    def row(r, i):
+        return r.node_ids[r.indices[0][r.indptr[0][i]:r.indptr[0][i + 1]]].tolist()
+    assert row(ra, 0) == row(rb, 2) and row(ra, 3) == row(rb, 0)
+    assert orc.sample_mfg(a, (5,), 77).indices[0].tolist() == ra.indices[0].tolist()
+    rc = orc.sample_mfg(a, (5,), 78)
+    assert [row(rc, i) for i in range(4)] != [row(ra, i) for i in range(4)]
+    # hop index enters the counter: the seed row differs between hop 0 and hop 1
+    rd = orc.sample_mfg(a, (5, 5), 77)
+    row0 = rd.node_ids[rd.indices[0][rd.indptr[0][0]:rd.indptr[0][1]]].tolist()
+    row1 = rd.node_ids[rd.indices[1][rd.indptr[1][0]:rd.indptr[1][1]]].tolist()
+    assert row0 == row(ra, 0) and row1 != row0
+    deg = int(indptr[11] - indptr[10])
+    assert oracle.sample_positions(deg, 5, 77, 10, 0) != oracle.sample_positions(deg, 5, 77, 11, 0)
+
+
+# ---------------------------------------------------------------------------------------------
+# uniformity (chi-square) through the whole sample_mfg path
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,k", [(8, 3), (12, 5), (40, 15)])
+def test_chi_square_uniform_subsets(n, k):
+    """Star graph: centre 0 with n leaves, fanout k < n, 30000 keys.  Inclusion counts per leaf
+    must fit k/n; for small C(n,k) the counts over all subsets must fit the uniform law.
+    The keys are fixed, so the test is deterministic; the bounds are the 1e-5 tails (a wrong index
+    range or a biased collision rule moves the statistic by orders of magnitude)."""
+    adj = [list(range(1, n + 1))] + [[0] for _ in range(n)]
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    trials = 30000
+    incl = np.zeros(n + 1, dtype=np.int64)
+    subsets = Counter()
+    first = np.zeros(n + 1, dtype=np.int64)
+    seeds = np.array([0], dtype=np.int32)
+    for key in range(trials):
+        r = orc.sample_mfg(seeds, (k,), key * 2654435761 + 12345)
+        picked = r.node_ids[r.indices[0]]
+        assert len(picked) == k
+        incl[picked] += 1
+        first[picked[0]] += 1
+        subsets[frozenset(picked.tolist())] += 1
+    # inclusion: each leaf is in the sample with probability k/n.  Counts are negatively
+    # correlated; the statistic sum (O-E)^2/E * (n-1)/(n-k) is ~ chi2(n-1) for uniform subsets.
+    exp = trials * k / n
+    x2 = float(((incl[1:] - exp) ** 2 / exp).sum()) * (n - 1) / (n - k)
+    assert x2 < stats.chi2.ppf(1 - 1e-5, n - 1), x2
+    assert incl[0] == 0
+    if math.comb(n, k) <= 1000:
+        c = math.comb(n, k)
+        e = trials / c
+        obs = np.array(list(subsets.values()) + [0] * (c - len(subsets)), dtype=np.float64)
+        x2s = float(((obs - e) ** 2 / e).sum())
+        assert stats.chi2.ppf(1e-5, c - 1) < x2s < stats.chi2.ppf(1 - 1e-5, c - 1), x2s
+
+
+# ---------------------------------------------------------------------------------------------
+# error reporting
+# ---------------------------------------------------------------------------------------------
+
+def test_status_codes():
+    adj = [[1, 2, 3], [0], [0], [0]]
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    assert orc.sample_mfg(np.array([0, 0], dtype=np.int32), (2,), 1).status == oracle.ST_DUP_SEED
+    assert orc.sample_mfg(np.array([4], dtype=np.int32), (2,), 1).status == oracle.ST_SEED_RANGE
+    assert orc.sample_mfg(np.array([0], dtype=np.int32), (3,), 1, node_capacity=3).status \
+        == oracle.ST_NODE_CAPACITY
+    assert orc.sample_mfg(np.array([0], dtype=np.int32), (3,), 1, edge_capacity=[2]).status \
+        == oracle.ST_EDGE_CAPACITY
+    assert (orc.local_of == -1).all()
+    assert orc.sample_mfg(np.array([0], dtype=np.int32), (3,), 1).status == 0
+
+
+def test_synthetic_workload_tiny(tiny_inputs):
+    """The smallest benchmark workload end to end, checked structurally."""
+    w, g, feat, batches = tiny_inputs
+    indptr, indices = g.indptr.numpy(), g.indices.numpy()
+    orc = oracle.Oracle(indptr, indices, feat.numpy())
+    for b, seeds in enumerate(batches):
+        r = orc.sample_mfg(seeds.numpy(), w.fanouts, 1234 + b)
+        assert r.status == 0
+        check_mfg(indptr, indices, seeds.numpy(), w.fanouts, r.node_ids, r.indptr, r.indices,
+                  r.num_nodes, r.num_edges)
+        assert np.array_equal(r.features.view(np.float32), feat.numpy()[r.node_ids])
