@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the mini-batch preparation path on one MI355X.
+
+A "step" is one prepared mini-batch: neighbour sampling over all hops, MFG block construction and
+the feature gather for one batch of seeds, everything resident in HBM.  Several batches share each
+set of launches (`--batches-per-call`), which is how independent batches are kept in flight.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload papers]
+
+Prints one JSON line (metric: sampled mini-batches/s) with a `roofline` object for the dominant
+kernel (the feature gather, HBM bound) and a `cpu_baseline` object (the CPU oracle timed on the
+host cores on a bounded sample of the same batches).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import threading
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(n, e, row_bytes):
+    """Compulsory reads + writes of one batch: seeds, two int64 indptr words per destination, the
+    chosen neighbour ids, feature rows in; block indptr / indices, node ids, feature rows out."""
+    L = len(e)
+    reads = 4 * n[0] + sum(16 * n[h] + 4 * e[h] for h in range(L)) + row_bytes * n[L]
+    writes = sum(4 * (n[h] + 1) + 4 * e[h] for h in range(L)) + 4 * n[L] + row_bytes * n[L]
+    return reads + writes
+
+
+def cpu_baseline(w, graph, feat, batches, keys, budget_s, threads, gpu_check):
+    """Times the oracle as it stands on `threads` host threads, each with its own scratch map,
+    over a bounded number of the same batches; also checks the first batches against the GPU."""
+    import numpy as np
+    import oracle
+    t0 = time.time()
+    h_indptr = graph.indptr.cpu().numpy()
+    h_indices = graph.indices.cpu().numpy()
+    h_feat = feat.cpu().numpy()
+    h_feat = h_feat.view(np.uint8).reshape(h_feat.shape[0], -1)
+    log(f"[cpu] host copies of graph and features: {time.time() - t0:.1f}s")
+    base = oracle.Oracle(h_indptr, h_indices, h_feat)
+    h_batches = [b.cpu().numpy() for b in batches]
+
+    t0 = time.time()
+    ref0 = base.sample_mfg(h_batches[0], w.fanouts, keys[0])
+    t_one = time.time() - t0
+    parity = gpu_check(ref0, 0)
+    per_thread = max(1, min(int(budget_s / max(t_one, 1e-4)), 4096))
+    n_total = per_thread * threads
+    workers = [base] + [base.clone_scratch() for _ in range(threads - 1)]
+    edges = [0] * threads
+
+    def run(t):
+        for q in range(per_thread):
+            i = (t * per_thread + q) % len(h_batches)
+            r = workers[t].sample_mfg(h_batches[i], w.fanouts, keys[i])
+            edges[t] += sum(r.num_edges)
+
+    ths = [threading.Thread(target=run, args=(t,)) for t in range(threads)]
+    t0 = time.time()
+    for t in ths:
+        t.start()
+    for t in ths:
+        t.join()
+    dt = time.time() - t0
+    return {
+        "value": n_total / dt, "unit": "batches/s", "cores": threads, "kind": "oracle",
+        "sample": f"{n_total} batches of workload '{w.name}' ({per_thread} per thread, {threads} threads, "
+                  f"one batch on one thread: {t_one * 1e3:.1f} ms)",
+        "sampled_edges_per_s": sum(edges) / dt, "parity_vs_gpu": parity,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="papers")
+    ap.add_argument("--batches-per-call", type=int, default=8)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--stages", action="store_true", help="extra untimed pass with every launch timed")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (batches are independent, so more GPUs would each "
+            "take their own batches of a replicated graph); run with --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2110_08450_amd import binding as smfg, synth
+
+    w = synth.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    graph = synth.make_graph(w, device=dev)
+    torch.cuda.synchronize()
+    log(f"[gen] graph '{w.name}': {graph.num_nodes} nodes, {graph.num_edges} directed edges, {time.time() - t0:.1f}s")
+    t0 = time.time()
+    feat = synth.make_features(w, device=dev)
+    batches = synth.make_seed_batches(w, device=dev)
+    torch.cuda.synchronize()
+    log(f"[gen] features {tuple(feat.shape)} {feat.dtype}, {len(batches)} seed batches, {time.time() - t0:.1f}s")
+    torch.cuda.empty_cache()
+
+    G = max(1, min(args.batches_per_call, smfg.MAX_BATCHES))
+    L = len(w.fanouts)
+    g = smfg.graph_create(graph.indptr, graph.indices, feat)
+    wss = [smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(G)]
+    outs = [smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)]
+    row_bytes = g.row_bytes
+
+    K = max(G, (args.steps // G) * G)
+    W = -(-args.warmup // G) * G if args.warmup > 0 else 0
+    keys = [synth.batch_rng_key(w, i) for i in range(len(batches))]
+    counts_all = torch.zeros((K + W, 2 * L + 2), dtype=torch.int64, device=dev)
+    stride = counts_all.stride(0) * 8
+
+    def run_calls(first, n):
+        for c in range(first, first + n, G):
+            idx = [(c + b) % len(batches) for b in range(G)]
+            for b in range(G):
+                outs[b].c.counts = counts_all.data_ptr() + (c + b) * stride
+            smfg.sample_mfg_many(g, wss, [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx], outs)
+
+    run_calls(0, W)
+    torch.cuda.synchronize()
+    smfg.profile_begin(1, K // G)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_calls(W, K)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = smfg.profile_end()
+
+    cnt = counts_all[W:].cpu().tolist()
+    assert all(c[2 * L + 1] == 0 for c in cnt), "a timed batch reported a device status"
+    n_final = sum(c[L] for c in cnt)
+    edges = sum(sum(c[L + 1:2 * L + 1]) for c in cnt)
+    alg = sum(algorithmic_bytes(c[:L + 1], c[L + 1:2 * L + 1], row_bytes) for c in cnt)
+    gather_ms, gather_launches = stages["gather"]
+    gather_bytes = 2 * row_bytes * n_final
+    gather_gbs = gather_bytes / (gather_ms * 1e-3) / 1e9 if gather_ms > 0 else 0.0
+
+    result = {
+        "metric": "sampled mini-batches/sec (MFG build + feature gather)",
+        "value": K / dt, "unit": "batches/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {graph.num_edges} directed edges, "
+                               f"features {w.feat_dim}x{str(w.feat_dtype).split('.')[-1]}, fanouts {list(w.fanouts)}, "
+                               f"batch {w.batch_size}", "batches_per_call": G,
+                   "mean_nodes_per_batch": n_final / K, "mean_edges_per_batch": edges / K},
+        "sampled_edges_per_s": edges / dt,
+        "gather_GBps": gather_gbs,
+        "path_algorithmic_GBps": alg / dt / 1e9,
+        "path_frac_of_hbm_peak": alg / dt / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": gather_ms / max(1, gather_launches),
+                     "algorithmic_bytes_per_launch": gather_bytes / max(1, gather_launches)},
+    }
+
+    if args.stages:
+        smfg.profile_begin(2, 64 * (K // G))
+        run_calls(W, K)
+        st = smfg.profile_end()
+        result["stage_ms_per_batch"] = {s: ms / K for s, (ms, _) in st.items()}
+
+    if not args.no_cpu:
+        import numpy as np
+
+        def gpu_check(ref, i):
+            outs[0].c.counts = counts_all.data_ptr()
+            smfg.sample_mfg(g, wss[0], batches[i], w.fanouts, keys[i], outs[0])
+            c = smfg.read_counts(outs[0])
+            n, e = c[:L + 1], c[L + 1:2 * L + 1]
+            ok = c == [int(x) for x in ref.counts]
+            ok = ok and np.array_equal(outs[0].node_ids[:n[L]].cpu().numpy(), ref.node_ids)
+            for h in range(L):
+                ok = ok and np.array_equal(outs[0].indptr[h][:n[h] + 1].cpu().numpy(), ref.indptr[h])
+                ok = ok and np.array_equal(outs[0].indices[h][:e[h]].cpu().numpy(), ref.indices[h])
+            got = outs[0].features[:n[L]].cpu().numpy().view(np.uint8).reshape(n[L], row_bytes)
+            return bool(ok and np.array_equal(got, ref.features))
+
+        threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
+        result["cpu_baseline"] = cpu_baseline(w, graph, feat, batches, keys, args.cpu_seconds, threads, gpu_check)
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

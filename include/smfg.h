@@ -1,0 +1,177 @@
+/*
+ * smfg - sampled mini-batch preparation for GNN training / inference on one AMD MI355X.
+ *
+ * C ABI of libsmfg.so.  The library computes, on the GPU, what the paper's batch-preparation
+ * step computes on CPU cores (paper section 4.1 and Listing 1, lines 2-3):
+ *
+ *   1. node-wise neighbour sampling: for every destination node take at most d_h of its
+ *      neighbours, uniformly, without replacement (section 2.2, "node-wise sampling";
+ *      section 4.1, first paragraph), one fanout d_h per hop;
+ *   2. construction of one bipartite block per hop with compact local node ids: destination
+ *      nodes keep the first local ids in their given order, every other node gets the next id
+ *      at its first appearance when scanning destinations in order and each destination's
+ *      samples in slot order (the MFG construction algorithm, procedure OneHopMFG); hops are
+ *      chained, the node list of hop h being the destination list of hop h+1 (section 4.1);
+ *   3. the feature slice xs = x[ids] for the final node list (Listing 1).
+ *
+ * Conventions fixed where the paper is silent:
+ *   - fanouts[0] belongs to hop 0, whose destinations are the seeds;
+ *   - a node with degree <= d_h contributes its whole CSR row in CSR order (no random draw);
+ *     otherwise d_h distinct row positions are chosen by Floyd's subset algorithm, slot s
+ *     holding the s-th pick;
+ *   - random words come from Philox4x32-10 (Salmon et al., SC'11) with key = (low, high) 32-bit
+ *     halves of rng_key and counter = (destination node, hop, s / 4, 0), word s % 4; a word r
+ *     gives an index in [0, m) as floor(r * m / 2^32);
+ *   - block h is a CSR keyed by destination: indptr[h] has n_h + 1 entries, indices[h] holds the
+ *     local ids of the sampled source nodes; destination i and source i are the same node.
+ * The result is a pure function of (graph, seeds, fanouts, rng_key).
+ *
+ * All "device" pointers are HIP device memory on the device that was current when the graph
+ * handle was created.  The caller allocates and frees every input and output buffer; handles
+ * own only their private scratch.  No function throws or aborts; every function returns SMFG_OK
+ * or a negative SMFG_ERR_* code.  Conditions only the GPU can see are reported as a positive
+ * SMFG_ST_* value in counts[2L+1]; outputs are then unspecified but nothing is written out of
+ * bounds.
+ */
+#ifndef SMFG_H_
+#define SMFG_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SMFG_MAX_LAYERS 8
+#define SMFG_MAX_FANOUT 32
+#define SMFG_MAX_BATCHES 8 /* batches per smfg_sample_mfg_many call */
+
+/* host-detected errors (return values) */
+#define SMFG_OK 0
+#define SMFG_ERR_INVALID_ARG (-1)
+#define SMFG_ERR_NULL_PTR (-2)
+#define SMFG_ERR_BAD_FANOUT (-3)      /* d < 1 or d > SMFG_MAX_FANOUT */
+#define SMFG_ERR_TOO_MANY_LAYERS (-4) /* L < 1 or L > SMFG_MAX_LAYERS */
+#define SMFG_ERR_TOO_MANY_SEEDS (-5)  /* more seeds than the workspace / output was sized for */
+#define SMFG_ERR_OOM (-6)             /* scratch allocation failed */
+#define SMFG_ERR_CAPACITY (-7)        /* output capacities exceed what the workspace supports */
+#define SMFG_ERR_HIP_BASE (-1000)     /* a HIP call failed: code = SMFG_ERR_HIP_BASE - hipError_t */
+
+/* device-detected conditions (value of counts[2L+1]) */
+#define SMFG_ST_OK 0
+#define SMFG_ST_NODE_CAPACITY 1     /* more distinct nodes than out->node_capacity */
+#define SMFG_ST_EDGE_CAPACITY 2     /* a block has more edges than out->edge_capacity[h] */
+#define SMFG_ST_TABLE_FULL 3        /* dedup table exhausted (only if node capacity is too) */
+#define SMFG_ST_SEED_OUT_OF_RANGE 4 /* a seed is < 0 or >= num_nodes */
+#define SMFG_ST_DUPLICATE_SEED 5    /* the seed list holds a node twice */
+
+typedef struct smfg_graph smfg_graph_t;         /* opaque; BORROWS the device arrays given to it */
+typedef struct smfg_workspace smfg_workspace_t; /* opaque; OWNS the scratch of one in-flight batch */
+
+/*
+ * Input graph G and feature matrix X (section 2.1: X is n x f, row v the features of node v;
+ * N(v) = {u : (u,v) in E}).  CSR row v = the neighbours N(v) of v; rows must not contain
+ * duplicates (else "without replacement" holds for positions, not neighbours).
+ *   d_indptr   device, int64 [num_nodes + 1], non-decreasing, d_indptr[0] = 0; each degree < 2^31
+ *   d_indices  device, int32 [num_edges], values in [0, num_nodes)
+ *   d_feat     device, row-major, row v at byte offset v * row_stride_bytes, the first
+ *              feat_dim * elem_bytes bytes of a row are its features (any elem_bytes >= 1;
+ *              rows are moved as opaque bytes, no conversion).  May be NULL: no gather then.
+ * num_nodes < 2^31.  The arrays are not copied and must outlive the handle.
+ */
+int smfg_graph_create(smfg_graph_t **out, int64_t num_nodes, int64_t num_edges,
+                      const int64_t *d_indptr, const int32_t *d_indices, const void *d_feat,
+                      int32_t feat_dim, int32_t elem_bytes, int64_t row_stride_bytes);
+int smfg_graph_destroy(smfg_graph_t *g);
+
+/*
+ * Worst-case sizes (host only, pure).  With disjoint neighbourhoods (section 3 draft text on
+ * neighbourhood expansion) n_{h+1} <= min(num_nodes, n_h (1 + d_h)) and E_h <= n_h d_h.
+ *   max_nodes host [L + 1], max_edges host [L].
+ */
+int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t *fanouts, int64_t num_nodes,
+                int64_t *max_nodes, int64_t *max_edges);
+
+/*
+ * Scratch for one batch in flight: dedup table (>= 2 slots per node of capacity), per-sample
+ * slot memory, per-row counters, scan partials.  Sized for up to max_seeds seeds, the given
+ * fanouts (a later call may use the same or smaller fanouts / fewer hops) and node_capacity
+ * distinct nodes (0 = the worst case of smfg_bounds).  Allocates device memory with hipMalloc.
+ */
+int smfg_workspace_create(smfg_workspace_t **out, const smfg_graph_t *g, int32_t max_seeds,
+                          int32_t L, const int32_t *fanouts, int64_t node_capacity);
+int smfg_workspace_destroy(smfg_workspace_t *ws);
+/* Bytes of device scratch the workspace holds (0 for NULL). */
+int64_t smfg_workspace_bytes(const smfg_workspace_t *ws);
+
+/* Output of one batch.  Every pointer is a caller-owned DEVICE buffer. */
+typedef struct {
+  int32_t *indptr[SMFG_MAX_LAYERS];  /* hop h: [node_capacity + 1]; n_h + 1 entries are written   */
+  int32_t *indices[SMFG_MAX_LAYERS]; /* hop h: [edge_capacity[h]]; E_h local source ids written   */
+  int32_t *node_ids;                 /* [node_capacity] global ids; N_h = the first n_h entries   */
+  void *features;                    /* [node_capacity x feat_dim*elem_bytes] dense rows, or NULL */
+  int64_t *counts;                   /* [2L+2]: n_0..n_L, E_0..E_{L-1}, status                    */
+  int64_t node_capacity;
+  int64_t edge_capacity[SMFG_MAX_LAYERS];
+} smfg_output_t;
+
+/*
+ * sample_mfg(graph, seeds, fanouts, rng_key) -> per-hop MFG blocks + node ids + gathered features.
+ * Enqueues all work on `hip_stream` (a hipStream_t, NULL = the default stream) and returns
+ * without waiting; nothing is copied to the host.  d_seeds: device int32 [num_seeds], distinct,
+ * in [0, num_nodes).  fanouts: host int32 [L].  `out` is read during the call only (the struct
+ * itself is host memory).  The workspace must not be used by another call until this one has
+ * finished on the GPU.  num_seeds = 0 is allowed (all counts 0).
+ */
+int smfg_sample_mfg(const smfg_graph_t *g, smfg_workspace_t *ws, const int32_t *d_seeds,
+                    int32_t num_seeds, const int32_t *fanouts, int32_t L, uint64_t rng_key,
+                    const smfg_output_t *out, void *hip_stream);
+
+/*
+ * The same for num_batches (1..SMFG_MAX_BATCHES) independent batches in one set of launches:
+ * batch b uses ws[b], d_seeds[b], num_seeds[b], rng_keys[b], outs[b]; all share the fanouts.
+ * Batches are independent units (section 4.2), so this is how several are kept in flight.
+ * Results are identical to num_batches separate smfg_sample_mfg calls.
+ */
+int smfg_sample_mfg_many(const smfg_graph_t *g, smfg_workspace_t *const *ws,
+                         const int32_t *const *d_seeds, const int32_t *num_seeds,
+                         const int32_t *fanouts, int32_t L, const uint64_t *rng_keys,
+                         const smfg_output_t *outs, int32_t num_batches, void *hip_stream);
+
+/*
+ * Only the gather xs = x[ids] (Listing 1): out rows j < *d_num_rows (a device int64) are copied
+ * from the graph's feature rows d_node_ids[j].  max_rows bounds the launch.  Asynchronous.
+ */
+int smfg_gather_rows(const smfg_graph_t *g, const int32_t *d_node_ids, const int64_t *d_num_rows,
+                     int64_t max_rows, void *d_out, void *hip_stream);
+
+/* Copies counts[0 .. 2L+2) to the host after synchronising the stream; returns SMFG_OK or, if the
+ * status word is non-zero, its (positive) SMFG_ST_* value. */
+int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, void *hip_stream);
+
+/*
+ * Stage timing for measurement (not thread safe; one profile at a time per process).
+ * Between begin and end, launches are bracketed by HIP events on the call's own stream:
+ * level 1 = only the feature gather launch, level 2 = every launch.  At most max_records
+ * launches are recorded, later ones run untimed.  smfg_profile_end synchronises the device,
+ * adds up the event-to-event milliseconds and the launch count per stage, and frees the events.
+ */
+#define SMFG_STAGE_CLEAR 0
+#define SMFG_STAGE_SEEDS 1
+#define SMFG_STAGE_SAMPLE 2
+#define SMFG_STAGE_FLAG 3
+#define SMFG_STAGE_SCAN_TILES 4
+#define SMFG_STAGE_PUBLISH 5
+#define SMFG_STAGE_ASSEMBLE 6
+#define SMFG_STAGE_GATHER 7
+#define SMFG_NUM_STAGES 8
+int smfg_profile_begin(int32_t level, int32_t max_records);
+int smfg_profile_end(double *stage_ms /* host [SMFG_NUM_STAGES] */,
+                     int64_t *stage_launches /* host [SMFG_NUM_STAGES] */);
+
+const char *smfg_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMFG_H_ */

@@ -1,0 +1,932 @@
+// libsmfg: sampled mini-batch preparation on gfx950 (MI355X).  Implements include/smfg.h.
+//
+// One hop h of one batch is five launches (all batches of a call share each launch through
+// blockIdx.y):
+//   sample_insert  per destination: degree, Floyd/Philox row positions, neighbour ids, and an
+//                  insert of each neighbour into the batch's dedup table carrying the sample's
+//                  scan position (section 4.1 "fusing sampling and MFG construction": the edge
+//                  is recorded the moment the neighbour is picked);
+//   flag_rows      which samples are the first appearance of their node (table value == own
+//                  position), as one bit mask per destination, plus per-tile totals;
+//   scan_tiles     exclusive scan of the tile totals, E_h and n_{h+1};
+//   scan_publish   per-row offsets (block indptr) and ranks of new nodes; the first appearance
+//                  of a node writes its final local id into the table and its global id into
+//                  node_ids (the auto-increment of procedure OneHopMFG, made order-independent:
+//                  the id is the rank of the first appearance in (destination, slot) order);
+//   assemble       block indices = final local id of every sample.
+// Then one gather launch copies the feature rows of the final node list (Listing 1, xs = x[ids]).
+//
+// The dedup table is open addressing over 64-bit slots (key << 32 | value).  A known node holds
+// its local id; a node met in the current hop holds kPend | position until it is published.
+// Claims use compare-and-swap on the whole slot, later samples of the same node use a 64-bit
+// atomic minimum, so the surviving value is the smallest position whatever the schedule.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <type_traits>
+
+#include "smfg.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileRows = 1024;             // destinations per scan tile
+constexpr uint32_t kPend = 0x80000000u;     // value bit: position of this hop, not yet a local id
+constexpr uint64_t kEmpty = ~0ull;
+
+struct BatchCtx {
+  const int32_t* seeds;
+  int64_t* counts;       // [2L+2]
+  uint64_t* table;
+  int32_t* node_ids;
+  int32_t* slot;         // [(destination, s)] -> table slot of that sample
+  int32_t* rowk;         // samples per destination
+  uint32_t* rowmask;     // first-appearance bits per destination
+  uint64_t* tile_sums;   // per tile: (edges << 32 | new nodes), later their exclusive scan
+  int32_t* blk_indptr;   // hop h
+  int32_t* blk_indices;  // hop h
+  uint8_t* features;
+  int64_t edge_capacity; // hop h
+  int32_t node_capacity;
+  int32_t num_seeds;
+  uint32_t key0, key1;
+  uint32_t table_shift;  // slot = hash >> shift
+  uint32_t table_mask;
+};
+
+struct Launch {
+  const int64_t* indptr;
+  const int32_t* indices;
+  const uint8_t* feat;
+  int64_t row_bytes;
+  int64_t row_stride;
+  int64_t num_nodes;
+  int32_t L;       // hops of this call (counts layout)
+  int32_t h;       // current hop
+  int32_t d;       // its fanout
+  int32_t G;       // batches
+  BatchCtx b[SMFG_MAX_BATCHES];
+};
+
+__device__ __forceinline__ int64_t status_of(const BatchCtx& B, int L) {
+  return __hip_atomic_load(&B.counts[2 * L + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void set_status(const BatchCtx& B, int L, int64_t code) {
+  unsigned long long* p = reinterpret_cast<unsigned long long*>(&B.counts[2 * L + 1]);
+  atomicCAS(p, 0ull, static_cast<unsigned long long>(code));
+}
+
+// ---- Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) -------------------------------------
+// Returns word `w` (0..3) of the block with counter (c0, c1, c2, 0) and key (k0, k1).
+__device__ __forceinline__ uint32_t philox_word(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t k0,
+                                                uint32_t k1, uint32_t w) {
+  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+  uint32_t c3 = 0u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0;
+    const uint32_t n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return w == 0 ? c0 : (w == 1 ? c1 : (w == 2 ? c2 : c3));
+}
+
+// ---- dedup table ----------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t hash_slot(uint32_t key, uint32_t shift) {
+  return (key * 0x9E3779B1u) >> shift;
+}
+
+// Inserts key with value `val` or lowers the stored value to `val`; returns the slot.
+// `existed` is set when the key was already there (used to detect duplicate seeds).
+__device__ __forceinline__ uint32_t table_insert_min(const BatchCtx& B, uint32_t key, uint32_t val,
+                                                     bool& existed, bool& full) {
+  unsigned long long* T = reinterpret_cast<unsigned long long*>(B.table);
+  const unsigned long long mine = (static_cast<unsigned long long>(key) << 32) | val;
+  uint32_t s = hash_slot(key, B.table_shift);
+  existed = false;
+  full = false;
+  for (uint32_t probes = 0; probes <= B.table_mask; ++probes) {
+    unsigned long long cur = __hip_atomic_load(&T[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (cur == kEmpty) {
+      cur = atomicCAS(&T[s], kEmpty, mine);
+      if (cur == kEmpty) return s;
+    }
+    if (static_cast<uint32_t>(cur >> 32) == key) {
+      existed = true;
+      if (static_cast<uint32_t>(cur) > val) atomicMin(&T[s], mine);
+      return s;
+    }
+    s = (s + 1) & B.table_mask;
+  }
+  full = true;
+  return 0;
+}
+
+// ---- kernels --------------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(kThreads) k_clear(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  const size_t n = static_cast<size_t>(B.table_mask) + 1;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x; i < n;
+       i += static_cast<size_t>(gridDim.x) * kThreads)
+    B.table[i] = kEmpty;
+  if (blockIdx.x == 0) {
+    const int m = 2 * P.L + 2;
+    for (int q = threadIdx.x; q < m; q += kThreads) B.counts[q] = (q == 0) ? B.num_seeds : 0;
+  }
+}
+
+// M starts with the destination nodes of hop 0 in the order given (procedure OneHopMFG).
+__global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  for (int i = blockIdx.x * kThreads + threadIdx.x; i < B.num_seeds; i += gridDim.x * kThreads) {
+    const int32_t v = B.seeds[i];
+    if (v < 0 || static_cast<int64_t>(v) >= P.num_nodes) {
+      set_status(B, P.L, SMFG_ST_SEED_OUT_OF_RANGE);
+      continue;
+    }
+    bool existed, full;
+    table_insert_min(B, static_cast<uint32_t>(v), static_cast<uint32_t>(i), existed, full);
+    if (existed) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
+    if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
+    B.node_ids[i] = v;
+  }
+}
+
+// GS lanes cooperate on one destination; lane s owns slot s.
+template <int GS>
+__global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int d = P.d;
+  constexpr int kGroups = kThreads / GS;
+  const int s = threadIdx.x & (GS - 1);
+  const int grp = threadIdx.x / GS;
+  const int gshift = (threadIdx.x & 63) & ~(GS - 1);
+  const unsigned long long gmask = (GS == 64) ? ~0ull : ((1ull << GS) - 1ull);
+
+  for (int i0 = blockIdx.x * kGroups; i0 < n; i0 += gridDim.x * kGroups) {
+    const int i = i0 + grp;
+    const bool row = i < n;
+    uint32_t v = 0, deg = 0;
+    int64_t a = 0;
+    if (row) {
+      v = static_cast<uint32_t>(B.node_ids[i]);
+      a = P.indptr[v];
+      deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
+    }
+    const bool floyd = row && deg > static_cast<uint32_t>(d);
+    const uint32_t k = floyd ? static_cast<uint32_t>(d) : deg;
+    uint32_t p = static_cast<uint32_t>(s);  // whole row in CSR order when deg <= d
+    uint32_t t = 0, j = 0;
+    if (floyd && s < d) {
+      const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), static_cast<uint32_t>(s) >> 2,
+                                     B.key0, B.key1, static_cast<uint32_t>(s) & 3u);
+      j = deg - static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
+      t = __umulhi(w, j + 1u);  // index in [0, j]
+    }
+    // Floyd's subset algorithm, resolved slot by slot: pick t_s unless an earlier slot holds it,
+    // then pick j_s.  The membership test is a linear search over the lanes (the array set).
+    for (int q = 0; q < d; ++q) {
+      const uint32_t tq = __shfl(t, q, GS);
+      const bool hit = floyd && s < q && p == tq;
+      const unsigned long long bal = (__ballot(hit) >> gshift) & gmask;
+      if (floyd && s == q) p = bal ? j : tq;
+    }
+    if (row && static_cast<uint32_t>(s) < k) {
+      const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
+      const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
+      bool existed, full;
+      const uint32_t sl = table_insert_min(B, g, kPend | pos, existed, full);
+      if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
+      B.slot[pos] = static_cast<int32_t>(sl);
+    }
+    if (row && s == 0) B.rowk[i] = static_cast<int32_t>(k);
+  }
+}
+
+__device__ __forceinline__ unsigned long long block_sum(unsigned long long x, unsigned long long* lds) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_down(x, o, 64);
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) lds[wave] = x;
+  __syncthreads();
+  unsigned long long r = 0;
+#pragma unroll
+  for (int w = 0; w < kThreads / 64; ++w) r += lds[w];
+  return r;
+}
+
+template <int GS>
+__global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int d = P.d;
+  constexpr int kGroups = kThreads / GS;
+  const int s = threadIdx.x & (GS - 1);
+  const int grp = threadIdx.x / GS;
+  const int gshift = (threadIdx.x & 63) & ~(GS - 1);
+  const unsigned long long gmask = (GS == 64) ? ~0ull : ((1ull << GS) - 1ull);
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    unsigned long long acc = 0;
+    for (int r0 = 0; r0 < kTileRows && tile * kTileRows + r0 < n; r0 += kGroups) {
+      const int i = tile * kTileRows + r0 + grp;
+      const bool row = i < n;
+      const int k = row ? B.rowk[i] : 0;
+      bool first = false;
+      if (s < k) {
+        const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
+        const uint64_t e = B.table[B.slot[pos]];
+        first = static_cast<uint32_t>(e) == (kPend | pos);
+      }
+      const uint32_t mask = static_cast<uint32_t>((__ballot(first) >> gshift) & gmask);
+      if (row && s == 0) {
+        B.rowmask[i] = mask;
+        acc += (static_cast<unsigned long long>(k) << 32) | static_cast<unsigned long long>(__popc(mask));
+      }
+    }
+    const unsigned long long tot = block_sum(acc, lds);
+    if (threadIdx.x == 0) B.tile_sums[tile] = tot;
+  }
+}
+
+// Exclusive scan over a block of kThreads values; returns the exclusive prefix, total in `total`.
+__device__ __forceinline__ unsigned long long block_exscan(unsigned long long x, unsigned long long* lds,
+                                                            unsigned long long& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned long long inc = x;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned long long y = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += y;
+  }
+  __syncthreads();
+  if (lane == 63) lds[wave] = inc;
+  __syncthreads();
+  unsigned long long base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kThreads / 64; ++w) {
+    const unsigned long long v = lds[w];
+    if (w < wave) base += v;
+    tot += v;
+  }
+  total = tot;
+  return base + inc - x;
+}
+
+__global__ void __launch_bounds__(kThreads) k_scan_tiles(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  unsigned long long carry = 0;
+  for (int t0 = 0; t0 < tiles; t0 += kThreads) {
+    const int t = t0 + threadIdx.x;
+    const unsigned long long x = t < tiles ? B.tile_sums[t] : 0ull;
+    unsigned long long total;
+    const unsigned long long ex = block_exscan(x, lds, total);
+    if (t < tiles) B.tile_sums[t] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    const int64_t edges = static_cast<int64_t>(carry >> 32);
+    const int64_t nodes = static_cast<int64_t>(n) + static_cast<int64_t>(carry & 0xFFFFFFFFull);
+    B.counts[P.L + 1 + P.h] = edges;
+    B.counts[P.h + 1] = nodes;
+    B.blk_indptr[n] = static_cast<int32_t>(edges);
+    if (nodes > B.node_capacity) set_status(B, P.L, SMFG_ST_NODE_CAPACITY);
+    else if (edges > B.edge_capacity) set_status(B, P.L, SMFG_ST_EDGE_CAPACITY);
+  }
+}
+
+// One thread per 4 consecutive destinations of a tile.
+__global__ void __launch_bounds__(kThreads) k_scan_publish(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int d = P.d;
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  static_assert(kTileRows == 4 * kThreads, "four rows per thread");
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const int i0 = tile * kTileRows + threadIdx.x * 4;
+    int k[4];
+    uint32_t m[4];
+    unsigned long long mine = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const bool row = i0 + r < n;
+      k[r] = row ? B.rowk[i0 + r] : 0;
+      m[r] = row ? B.rowmask[i0 + r] : 0u;
+      mine += (static_cast<unsigned long long>(k[r]) << 32) | static_cast<unsigned long long>(__popc(m[r]));
+    }
+    unsigned long long total;
+    unsigned long long pre = B.tile_sums[tile] + block_exscan(mine, lds, total);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = i0 + r;
+      if (i < n) {
+        B.blk_indptr[i] = static_cast<int32_t>(pre >> 32);
+        uint32_t local = static_cast<uint32_t>(n) + static_cast<uint32_t>(pre & 0xFFFFFFFFull);
+        uint32_t bits = m[r];
+        while (bits) {
+          const int sbit = __ffs(bits) - 1;
+          bits &= bits - 1;
+          const int32_t sl = B.slot[static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(sbit)];
+          const uint32_t key = static_cast<uint32_t>(B.table[sl] >> 32);
+          B.table[sl] = (static_cast<uint64_t>(key) << 32) | local;
+          B.node_ids[local] = static_cast<int32_t>(key);
+          ++local;
+        }
+      }
+      pre += (static_cast<unsigned long long>(k[r]) << 32) | static_cast<unsigned long long>(__popc(m[r]));
+    }
+    __syncthreads();
+  }
+}
+
+template <int GS>
+__global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int d = P.d;
+  constexpr int kGroups = kThreads / GS;
+  const int s = threadIdx.x & (GS - 1);
+  const int grp = threadIdx.x / GS;
+  for (int i = blockIdx.x * kGroups + grp; i < n; i += gridDim.x * kGroups) {
+    const int k = B.rowk[i];
+    if (s < k) {
+      const int32_t base = B.blk_indptr[i];
+      const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
+      B.blk_indices[base + s] = static_cast<int32_t>(static_cast<uint32_t>(B.table[B.slot[pos]]));
+    }
+  }
+}
+
+// Rows are moved as vectors of VEC bytes; the output is addressed as one flat vector array so
+// stores are fully coalesced, and the lanes that share a row read one contiguous span of it.
+template <typename V>
+__device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, int64_t row_stride,
+                                            uint32_t vec_per_row, const int32_t* __restrict__ ids,
+                                            int64_t n, uint8_t* __restrict__ out) {
+  constexpr int U = 4;
+  const uint64_t total = static_cast<uint64_t>(n) * vec_per_row;
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kThreads;
+  V* __restrict__ o = reinterpret_cast<V*>(out);
+  for (uint64_t base = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x; base < total;
+       base += stride * U) {
+    V val[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t idx = base + static_cast<uint64_t>(u) * stride;
+      if (idx < total) {
+        const uint32_t jrow = static_cast<uint32_t>(idx / vec_per_row);
+        const uint32_t c = static_cast<uint32_t>(idx - static_cast<uint64_t>(jrow) * vec_per_row);
+        const V* src = reinterpret_cast<const V*>(feat + static_cast<int64_t>(ids[jrow]) * row_stride);
+        val[u] = __builtin_nontemporal_load(src + c);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t idx = base + static_cast<uint64_t>(u) * stride;
+      if (idx < total) __builtin_nontemporal_store(val[u], o + idx);
+    }
+  }
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename V>
+__global__ void __launch_bounds__(kThreads) k_gather(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), B.node_ids,
+                 B.counts[P.L], B.features);
+}
+
+template <typename V>
+__global__ void __launch_bounds__(kThreads) k_gather_plain(const uint8_t* feat, int64_t row_bytes,
+                                                           int64_t row_stride, const int32_t* ids,
+                                                           const int64_t* num_rows, int64_t max_rows,
+                                                           uint8_t* out) {
+  int64_t n = *num_rows;
+  if (n > max_rows) n = max_rows;
+  if (n < 0) n = 0;
+  gather_rows<V>(feat, row_stride, static_cast<uint32_t>(row_bytes / sizeof(V)), ids, n, out);
+}
+
+// ---- host side --------------------------------------------------------------------------------
+
+inline int hip_err(hipError_t e) { return e == hipSuccess ? SMFG_OK : SMFG_ERR_HIP_BASE - static_cast<int>(e); }
+
+inline int group_size(int d) { return d <= 4 ? 4 : d <= 8 ? 8 : d <= 16 ? 16 : 32; }
+
+inline int vec_bytes(uintptr_t a, uintptr_t b, int64_t row_bytes, int64_t row_stride) {
+  const uint64_t x = static_cast<uint64_t>(a) | static_cast<uint64_t>(b) | static_cast<uint64_t>(row_bytes) |
+                     static_cast<uint64_t>(row_stride);
+  if ((x & 15) == 0) return 16;
+  if ((x & 7) == 0) return 8;
+  if ((x & 3) == 0) return 4;
+  if ((x & 1) == 0) return 2;
+  return 1;
+}
+
+// Optional event bracketing of launches (smfg_profile_begin / smfg_profile_end).
+struct Profiler {
+  int level = 0;
+  int max_records = 0;
+  int used = 0;
+  hipEvent_t* ev = nullptr;  // 2 per record
+  int* stage = nullptr;
+} g_prof;
+
+struct StageTimer {
+  int rec = -1;
+  hipStream_t st;
+  StageTimer(int stage, hipStream_t s) : st(s) {
+    if (g_prof.level == 0) return;
+    if (g_prof.level == 1 && stage != SMFG_STAGE_GATHER) return;
+    if (g_prof.used >= g_prof.max_records) return;
+    rec = g_prof.used++;
+    g_prof.stage[rec] = stage;
+    (void)hipEventRecord(g_prof.ev[2 * rec], st);
+  }
+  ~StageTimer() {
+    if (rec >= 0) (void)hipEventRecord(g_prof.ev[2 * rec + 1], st);
+  }
+};
+
+void profiler_free() {
+  for (int i = 0; i < 2 * g_prof.max_records; ++i)
+    if (g_prof.ev && g_prof.ev[i]) (void)hipEventDestroy(g_prof.ev[i]);
+  std::free(g_prof.ev);
+  std::free(g_prof.stage);
+  g_prof = Profiler();
+}
+
+inline unsigned blocks_for(int64_t work_items, int64_t per_block, unsigned cap) {
+  int64_t b = (work_items + per_block - 1) / per_block;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return static_cast<unsigned>(b);
+}
+
+}  // namespace
+
+struct smfg_graph {
+  int64_t num_nodes, num_edges;
+  const int64_t* indptr;
+  const int32_t* indices;
+  const uint8_t* feat;
+  int64_t row_bytes, row_stride;
+  int device;
+};
+
+struct smfg_workspace {
+  int device;
+  int32_t max_seeds, L;
+  int32_t fanouts[SMFG_MAX_LAYERS];
+  int64_t node_capacity;
+  int64_t slot_entries;  // capacity of `slot`
+  int64_t bytes;
+  uint32_t table_log2;
+  void* slab;
+  uint64_t* table;
+  int32_t* slot;
+  int32_t* rowk;
+  uint32_t* rowmask;
+  uint64_t* tile_sums;
+};
+
+namespace {
+
+// Largest padded (destination, slot) index space any hop can need, given a node capacity.
+int64_t slot_entries_needed(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t num_nodes,
+                            int64_t node_capacity) {
+  int64_t n = num_seeds < num_nodes ? num_seeds : num_nodes, need = 0;
+  for (int h = 0; h < L; ++h) {
+    if (n > node_capacity) n = node_capacity;
+    const int64_t e = n * fanouts[h];
+    if (e > need) need = e;
+    n = n + e;
+    if (n > num_nodes) n = num_nodes;
+  }
+  return need;
+}
+
+int check_fanouts(int32_t L, const int32_t* fanouts) {
+  if (L < 1 || L > SMFG_MAX_LAYERS) return SMFG_ERR_TOO_MANY_LAYERS;
+  if (!fanouts) return SMFG_ERR_NULL_PTR;
+  for (int h = 0; h < L; ++h)
+    if (fanouts[h] < 1 || fanouts[h] > SMFG_MAX_FANOUT) return SMFG_ERR_BAD_FANOUT;
+  return SMFG_OK;
+}
+
+template <typename F>
+void launch_by_group(int gs, F&& f) {
+  switch (gs) {
+    case 4: f(std::integral_constant<int, 4>()); break;
+    case 8: f(std::integral_constant<int, 8>()); break;
+    case 16: f(std::integral_constant<int, 16>()); break;
+    default: f(std::integral_constant<int, 32>()); break;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int smfg_graph_create(smfg_graph_t** out, int64_t num_nodes, int64_t num_edges, const int64_t* d_indptr,
+                      const int32_t* d_indices, const void* d_feat, int32_t feat_dim, int32_t elem_bytes,
+                      int64_t row_stride_bytes) {
+  if (!out) return SMFG_ERR_NULL_PTR;
+  *out = nullptr;
+  if (!d_indptr || (num_edges > 0 && !d_indices)) return SMFG_ERR_NULL_PTR;
+  if (num_nodes < 0 || num_nodes >= (1ll << 31) || num_edges < 0) return SMFG_ERR_INVALID_ARG;
+  int64_t row_bytes = 0;
+  if (d_feat) {
+    if (feat_dim < 1 || elem_bytes < 1) return SMFG_ERR_INVALID_ARG;
+    row_bytes = static_cast<int64_t>(feat_dim) * elem_bytes;
+    if (row_stride_bytes < row_bytes) return SMFG_ERR_INVALID_ARG;
+  }
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_err(e);
+  smfg_graph* g = new (std::nothrow) smfg_graph;
+  if (!g) return SMFG_ERR_OOM;
+  g->num_nodes = num_nodes;
+  g->num_edges = num_edges;
+  g->indptr = d_indptr;
+  g->indices = d_indices;
+  g->feat = static_cast<const uint8_t*>(d_feat);
+  g->row_bytes = row_bytes;
+  g->row_stride = d_feat ? row_stride_bytes : 0;
+  g->device = dev;
+  *out = g;
+  return SMFG_OK;
+}
+
+int smfg_graph_destroy(smfg_graph_t* g) {
+  delete g;
+  return SMFG_OK;
+}
+
+int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t num_nodes, int64_t* max_nodes,
+                int64_t* max_edges) {
+  int rc = check_fanouts(L, fanouts);
+  if (rc != SMFG_OK) return rc;
+  if (!max_nodes || !max_edges) return SMFG_ERR_NULL_PTR;
+  if (num_seeds < 0 || num_nodes < 0) return SMFG_ERR_INVALID_ARG;
+  int64_t n = num_seeds < num_nodes ? num_seeds : num_nodes;
+  max_nodes[0] = n;
+  for (int h = 0; h < L; ++h) {
+    max_edges[h] = n * fanouts[h];
+    n = n + max_edges[h];
+    if (n > num_nodes) n = num_nodes;
+    max_nodes[h + 1] = n;
+  }
+  return SMFG_OK;
+}
+
+int smfg_workspace_create(smfg_workspace_t** out, const smfg_graph_t* g, int32_t max_seeds, int32_t L,
+                          const int32_t* fanouts, int64_t node_capacity) {
+  if (!out) return SMFG_ERR_NULL_PTR;
+  *out = nullptr;
+  if (!g) return SMFG_ERR_NULL_PTR;
+  int rc = check_fanouts(L, fanouts);
+  if (rc != SMFG_OK) return rc;
+  if (max_seeds < 0 || node_capacity < 0) return SMFG_ERR_INVALID_ARG;
+  int64_t mn[SMFG_MAX_LAYERS + 1], me[SMFG_MAX_LAYERS];
+  smfg_bounds(max_seeds, L, fanouts, g->num_nodes, mn, me);
+  if (node_capacity == 0 || node_capacity > mn[L]) node_capacity = mn[L];
+  if (node_capacity < 1) node_capacity = 1;
+  if (node_capacity < mn[0]) return SMFG_ERR_TOO_MANY_SEEDS;
+  const int64_t slots = slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity);
+  if (slots >= (1ll << 31) || node_capacity >= (1ll << 30)) return SMFG_ERR_CAPACITY;
+
+  uint32_t lg = 10;
+  while ((1ll << lg) < 2 * node_capacity) ++lg;
+
+  smfg_workspace* ws = new (std::nothrow) smfg_workspace;
+  if (!ws) return SMFG_ERR_OOM;
+  std::memset(ws, 0, sizeof(*ws));
+  ws->device = g->device;
+  ws->max_seeds = max_seeds;
+  ws->L = L;
+  for (int h = 0; h < L; ++h) ws->fanouts[h] = fanouts[h];
+  ws->node_capacity = node_capacity;
+  ws->slot_entries = slots > 0 ? slots : 1;
+  ws->table_log2 = lg;
+
+  auto align = [](int64_t x) { return (x + 255) & ~int64_t(255); };
+  const int64_t tiles = (node_capacity + kTileRows - 1) / kTileRows + 1;
+  const int64_t b_table = align((int64_t(1) << lg) * 8);
+  const int64_t b_slot = align(ws->slot_entries * 4);
+  const int64_t b_rowk = align((node_capacity + 4) * 4);
+  const int64_t b_mask = align((node_capacity + 4) * 4);
+  const int64_t b_tiles = align(tiles * 8);
+  ws->bytes = b_table + b_slot + b_rowk + b_mask + b_tiles;
+  int cur = 0;
+  (void)hipGetDevice(&cur);
+  if (cur != g->device) (void)hipSetDevice(g->device);
+  hipError_t e = hipMalloc(&ws->slab, static_cast<size_t>(ws->bytes));
+  if (cur != g->device) (void)hipSetDevice(cur);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    delete ws;
+    return SMFG_ERR_OOM;
+  }
+  uint8_t* p = static_cast<uint8_t*>(ws->slab);
+  ws->table = reinterpret_cast<uint64_t*>(p); p += b_table;
+  ws->slot = reinterpret_cast<int32_t*>(p); p += b_slot;
+  ws->rowk = reinterpret_cast<int32_t*>(p); p += b_rowk;
+  ws->rowmask = reinterpret_cast<uint32_t*>(p); p += b_mask;
+  ws->tile_sums = reinterpret_cast<uint64_t*>(p);
+  *out = ws;
+  return SMFG_OK;
+}
+
+int smfg_workspace_destroy(smfg_workspace_t* ws) {
+  if (!ws) return SMFG_OK;
+  hipError_t e = hipFree(ws->slab);
+  delete ws;
+  return hip_err(e);
+}
+
+int64_t smfg_workspace_bytes(const smfg_workspace_t* ws) { return ws ? ws->bytes : 0; }
+
+int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, const int32_t* const* d_seeds,
+                         const int32_t* num_seeds, const int32_t* fanouts, int32_t L, const uint64_t* rng_keys,
+                         const smfg_output_t* outs, int32_t num_batches, void* hip_stream) {
+  if (!g || !ws || !d_seeds || !num_seeds || !rng_keys || !outs) return SMFG_ERR_NULL_PTR;
+  int rc = check_fanouts(L, fanouts);
+  if (rc != SMFG_OK) return rc;
+  if (num_batches < 1 || num_batches > SMFG_MAX_BATCHES) return SMFG_ERR_INVALID_ARG;
+
+  Launch P;
+  std::memset(&P, 0, sizeof(P));
+  P.indptr = g->indptr;
+  P.indices = g->indices;
+  P.feat = g->feat;
+  P.row_bytes = g->row_bytes;
+  P.row_stride = g->row_stride;
+  P.num_nodes = g->num_nodes;
+  P.L = L;
+  P.G = num_batches;
+
+  int64_t max_n[SMFG_MAX_LAYERS + 1];  // per hop, the largest destination count over the batches
+  for (int h = 0; h <= L; ++h) max_n[h] = 0;
+  uint32_t max_table_log2 = 0;
+  int32_t max_seeds = 0;
+  bool want_feat = false;
+  int vb = 16;
+
+  for (int b = 0; b < num_batches; ++b) {
+    const smfg_workspace* w = ws[b];
+    const smfg_output_t& o = outs[b];
+    if (!w) return SMFG_ERR_NULL_PTR;
+    for (int c = 0; c < b; ++c)
+      if (ws[c] == w) return SMFG_ERR_INVALID_ARG;
+    if (w->device != g->device) return SMFG_ERR_INVALID_ARG;
+    if (num_seeds[b] < 0) return SMFG_ERR_INVALID_ARG;
+    if (num_seeds[b] > 0 && !d_seeds[b]) return SMFG_ERR_NULL_PTR;
+    if (!o.node_ids || !o.counts) return SMFG_ERR_NULL_PTR;
+    for (int h = 0; h < L; ++h) {
+      if (!o.indptr[h] || !o.indices[h]) return SMFG_ERR_NULL_PTR;
+      if (o.edge_capacity[h] < 0) return SMFG_ERR_INVALID_ARG;
+    }
+    if (o.node_capacity < 1) return SMFG_ERR_INVALID_ARG;
+    if (num_seeds[b] > w->max_seeds || num_seeds[b] > o.node_capacity) return SMFG_ERR_TOO_MANY_SEEDS;
+    if (o.node_capacity > w->node_capacity) return SMFG_ERR_CAPACITY;
+    if (slot_entries_needed(num_seeds[b], L, fanouts, g->num_nodes, o.node_capacity) > w->slot_entries)
+      return SMFG_ERR_CAPACITY;
+    if (g->feat && o.features) {
+      want_feat = true;
+      const int v = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(o.features),
+                              g->row_bytes, g->row_stride);
+      if (v < vb) vb = v;
+    } else if (b > 0 && want_feat) {
+      return SMFG_ERR_INVALID_ARG;  // either every batch gathers or none
+    }
+    if (b > 0 && !want_feat && g->feat && o.features) return SMFG_ERR_INVALID_ARG;
+
+    BatchCtx& B = P.b[b];
+    B.seeds = d_seeds[b];
+    B.counts = o.counts;
+    B.table = w->table;
+    B.node_ids = o.node_ids;
+    B.slot = w->slot;
+    B.rowk = w->rowk;
+    B.rowmask = w->rowmask;
+    B.tile_sums = w->tile_sums;
+    B.features = static_cast<uint8_t*>(o.features);
+    B.node_capacity = static_cast<int32_t>(o.node_capacity);
+    B.num_seeds = num_seeds[b];
+    B.key0 = static_cast<uint32_t>(rng_keys[b]);
+    B.key1 = static_cast<uint32_t>(rng_keys[b] >> 32);
+    B.table_shift = 32u - w->table_log2;
+    B.table_mask = static_cast<uint32_t>((1ull << w->table_log2) - 1ull);
+    if (w->table_log2 > max_table_log2) max_table_log2 = w->table_log2;
+    if (num_seeds[b] > max_seeds) max_seeds = num_seeds[b];
+
+    int64_t n = num_seeds[b] < g->num_nodes ? num_seeds[b] : g->num_nodes;
+    for (int h = 0; h <= L; ++h) {
+      if (n > o.node_capacity) n = o.node_capacity;
+      if (n > max_n[h]) max_n[h] = n;
+      if (h < L) {
+        n = n + n * fanouts[h];
+        if (n > g->num_nodes) n = g->num_nodes;
+      }
+    }
+  }
+
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int cur = 0;
+  (void)hipGetDevice(&cur);
+  if (cur != g->device) (void)hipSetDevice(g->device);
+  const unsigned G = static_cast<unsigned>(num_batches);
+  constexpr unsigned kCap = 4096;
+
+  { StageTimer t_(SMFG_STAGE_CLEAR, st);
+  k_clear<<<dim3(blocks_for(int64_t(1) << max_table_log2, kThreads * 8, 2048), G), kThreads, 0, st>>>(P); }
+  { StageTimer t_(SMFG_STAGE_SEEDS, st);
+  k_insert_seeds<<<dim3(blocks_for(max_seeds, kThreads, kCap), G), kThreads, 0, st>>>(P); }
+  for (int h = 0; h < L; ++h) {
+    P.h = h;
+    P.d = fanouts[h];
+    for (int b = 0; b < num_batches; ++b) {
+      P.b[b].blk_indptr = outs[b].indptr[h];
+      P.b[b].blk_indices = outs[b].indices[h];
+      P.b[b].edge_capacity = outs[b].edge_capacity[h];
+    }
+    const int gs = group_size(P.d);
+    const int64_t rows = max_n[h];
+    const unsigned row_blocks = blocks_for(rows, kThreads / gs, kCap);
+    const unsigned tile_blocks = blocks_for(rows, kTileRows, kCap);
+    launch_by_group(gs, [&](auto GS) {
+      {
+        StageTimer t_(SMFG_STAGE_SAMPLE, st);
+        k_sample_insert<decltype(GS)::value><<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_FLAG, st);
+        k_flag_rows<decltype(GS)::value><<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
+      }
+    });
+    {
+      StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
+      k_scan_tiles<<<dim3(1, G), kThreads, 0, st>>>(P);
+    }
+    {
+      StageTimer t_(SMFG_STAGE_PUBLISH, st);
+      k_scan_publish<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
+    }
+    launch_by_group(gs, [&](auto GS) {
+      StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
+      k_assemble<decltype(GS)::value><<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
+    });
+  }
+  if (want_feat) {
+    const int64_t vecs = max_n[L] * (g->row_bytes / vb);
+    const unsigned gb = blocks_for(vecs, kThreads * 4, 8192);
+    StageTimer t_(SMFG_STAGE_GATHER, st);
+    switch (vb) {
+      case 16: k_gather<u32x4><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+      case 8: k_gather<u32x2><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+      case 4: k_gather<uint32_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+      case 2: k_gather<uint16_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+      default: k_gather<uint8_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (cur != g->device) (void)hipSetDevice(cur);
+  return hip_err(e);
+}
+
+int smfg_sample_mfg(const smfg_graph_t* g, smfg_workspace_t* ws, const int32_t* d_seeds, int32_t num_seeds,
+                    const int32_t* fanouts, int32_t L, uint64_t rng_key, const smfg_output_t* out,
+                    void* hip_stream) {
+  if (!out) return SMFG_ERR_NULL_PTR;
+  return smfg_sample_mfg_many(g, &ws, &d_seeds, &num_seeds, fanouts, L, &rng_key, out, 1, hip_stream);
+}
+
+int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int64_t* d_num_rows,
+                     int64_t max_rows, void* d_out, void* hip_stream) {
+  if (!g || !d_node_ids || !d_num_rows || !d_out) return SMFG_ERR_NULL_PTR;
+  if (!g->feat) return SMFG_ERR_INVALID_ARG;
+  if (max_rows < 0 || max_rows >= (1ll << 31)) return SMFG_ERR_INVALID_ARG;
+  if (max_rows == 0) return SMFG_OK;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int vb = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(d_out), g->row_bytes,
+                           g->row_stride);
+  const unsigned gb = blocks_for(max_rows * (g->row_bytes / vb), kThreads * 4, 8192);
+  uint8_t* o = static_cast<uint8_t*>(d_out);
+  int cur = 0;
+  (void)hipGetDevice(&cur);
+  if (cur != g->device) (void)hipSetDevice(g->device);
+  switch (vb) {
+    case 16: k_gather_plain<u32x4><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
+    case 8: k_gather_plain<u32x2><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
+    case 4: k_gather_plain<uint32_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
+    case 2: k_gather_plain<uint16_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
+    default: k_gather_plain<uint8_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
+  }
+  hipError_t e = hipGetLastError();
+  if (cur != g->device) (void)hipSetDevice(cur);
+  return hip_err(e);
+}
+
+int smfg_read_counts(const smfg_output_t* out, int32_t L, int64_t* h_counts, void* hip_stream) {
+  if (!out || !out->counts || !h_counts) return SMFG_ERR_NULL_PTR;
+  if (L < 1 || L > SMFG_MAX_LAYERS) return SMFG_ERR_TOO_MANY_LAYERS;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipMemcpyAsync(h_counts, out->counts, sizeof(int64_t) * (2 * L + 2), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return hip_err(e);
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return hip_err(e);
+  return static_cast<int>(h_counts[2 * L + 1]);
+}
+
+int smfg_profile_begin(int32_t level, int32_t max_records) {
+  if (level < 0 || level > 2 || max_records < 0) return SMFG_ERR_INVALID_ARG;
+  profiler_free();
+  if (level == 0 || max_records == 0) return SMFG_OK;
+  g_prof.ev = static_cast<hipEvent_t*>(std::calloc(2 * static_cast<size_t>(max_records), sizeof(hipEvent_t)));
+  g_prof.stage = static_cast<int*>(std::calloc(static_cast<size_t>(max_records), sizeof(int)));
+  if (!g_prof.ev || !g_prof.stage) {
+    profiler_free();
+    return SMFG_ERR_OOM;
+  }
+  g_prof.max_records = max_records;
+  for (int i = 0; i < 2 * max_records; ++i) {
+    hipError_t e = hipEventCreate(&g_prof.ev[i]);
+    if (e != hipSuccess) {
+      profiler_free();
+      return hip_err(e);
+    }
+  }
+  g_prof.level = level;
+  return SMFG_OK;
+}
+
+int smfg_profile_end(double* stage_ms, int64_t* stage_launches) {
+  if (!stage_ms || !stage_launches) return SMFG_ERR_NULL_PTR;
+  for (int s = 0; s < SMFG_NUM_STAGES; ++s) {
+    stage_ms[s] = 0.0;
+    stage_launches[s] = 0;
+  }
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    profiler_free();
+    return hip_err(e);
+  }
+  for (int r = 0; r < g_prof.used; ++r) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, g_prof.ev[2 * r], g_prof.ev[2 * r + 1]);
+    if (e != hipSuccess) {
+      profiler_free();
+      return hip_err(e);
+    }
+    stage_ms[g_prof.stage[r]] += ms;
+    stage_launches[g_prof.stage[r]] += 1;
+  }
+  profiler_free();
+  return SMFG_OK;
+}
+
+const char* smfg_strerror(int code) {
+  switch (code) {
+    case SMFG_OK: return "ok";
+    case SMFG_ERR_INVALID_ARG: return "invalid argument";
+    case SMFG_ERR_NULL_PTR: return "null pointer";
+    case SMFG_ERR_BAD_FANOUT: return "fanout out of range [1, SMFG_MAX_FANOUT]";
+    case SMFG_ERR_TOO_MANY_LAYERS: return "number of hops out of range [1, SMFG_MAX_LAYERS]";
+    case SMFG_ERR_TOO_MANY_SEEDS: return "more seeds than the workspace or output capacity";
+    case SMFG_ERR_OOM: return "out of memory";
+    case SMFG_ERR_CAPACITY: return "requested capacity exceeds what the workspace supports";
+    case SMFG_ST_NODE_CAPACITY: return "device: node capacity exceeded";
+    case SMFG_ST_EDGE_CAPACITY: return "device: edge capacity exceeded";
+    case SMFG_ST_TABLE_FULL: return "device: dedup table full";
+    case SMFG_ST_SEED_OUT_OF_RANGE: return "device: seed out of range";
+    case SMFG_ST_DUPLICATE_SEED: return "device: duplicate seed";
+    default: return code <= SMFG_ERR_HIP_BASE ? "HIP runtime error" : "unknown code";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2110_08450_amd import binding as smfg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "smfg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(smfg_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert sorted(smfg.EXPORTS) == names
+    lib = ctypes.CDLL(smfg.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_bounds_and_host_validation():
+    mn, me = smfg.bounds(1024, (15, 10, 5), 111_000_000)
+    assert mn == [1024, 16384, 180224, 1081344] and me == [15360, 163840, 901120]
+    mn, me = smfg.bounds(1024, (15, 10, 5), 169_000)        # capped by the graph size
+    assert mn[-1] == 169_000 and mn[2] == 169_000
+    for bad, code in [((0,), smfg.ERR_BAD_FANOUT), ((33,), smfg.ERR_BAD_FANOUT),
+                      ((), smfg.ERR_TOO_MANY_LAYERS), ((1,) * 9, smfg.ERR_TOO_MANY_LAYERS)]:
+        with pytest.raises(smfg.SmfgError) as ei:
+            smfg.bounds(4, bad, 100)
+        assert ei.value.code == code
+    assert "fanout" in smfg.strerror(smfg.ERR_BAD_FANOUT)
+    assert "duplicate" in smfg.strerror(smfg.ST_DUPLICATE_SEED)
+
+
+def test_oracle_and_library_agree_on_bounds():
+    import oracle
+    for seeds, fan, n in [(256, (10, 5), 10_000), (4096, (20, 20, 20), 111_000_000), (5, (32,), 20)]:
+        assert tuple(smfg.bounds(seeds, fan, n)) == tuple(oracle.worst_case(seeds, fan, n))

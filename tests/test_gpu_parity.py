@@ -1,0 +1,214 @@
+"""HIP library vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import check_mfg, csr_from_adj, random_simple_graph
+from paper_2110_08450_amd import binding as smfg
+from paper_2110_08450_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+class GpuGraph:
+    def __init__(self, indptr, indices, feat):
+        self.h_indptr, self.h_indices, self.h_feat = indptr, indices, feat
+        self.indptr = torch.from_numpy(np.ascontiguousarray(indptr)).to(DEV)
+        self.indices = torch.from_numpy(np.ascontiguousarray(indices)).to(DEV)
+        self.feat = torch.from_numpy(feat).to(DEV) if feat is not None else None
+        self.g = smfg.graph_create(self.indptr, self.indices, self.feat)
+        self.oracle = oracle.Oracle(indptr, indices,
+                                    feat.view(np.uint8).reshape(feat.shape[0], -1) if feat is not None else None)
+
+
+def fetch(out, L):
+    """Device outputs -> host arrays trimmed to the reported counts."""
+    c = smfg.read_counts(out, check=False)
+    n, e, st = c[:L + 1], c[L + 1:2 * L + 1], c[2 * L + 1]
+    if st != 0:
+        return dict(status=st, counts=c)
+    res = dict(status=0, counts=c, n=n, e=e,
+               node_ids=out.node_ids[:n[L]].cpu().numpy(),
+               indptr=[out.indptr[h][:n[h] + 1].cpu().numpy() for h in range(L)],
+               indices=[out.indices[h][:e[h]].cpu().numpy() for h in range(L)])
+    if out.features is not None:
+        rb = out.features.shape[1] * out.features.element_size()
+        res["features"] = out.features[:n[L]].cpu().numpy().view(np.uint8).reshape(n[L], rb)
+    return res
+
+
+def assert_same(res, ref, L):
+    """Bit-exact: counts, node ids, block indptr / indices, feature bytes."""
+    assert res["status"] == 0 and ref.status == 0
+    assert res["counts"] == [int(x) for x in ref.counts]
+    assert np.array_equal(res["node_ids"], ref.node_ids)
+    for h in range(L):
+        assert np.array_equal(res["indptr"][h], ref.indptr[h]), f"indptr hop {h}"
+        assert np.array_equal(res["indices"][h], ref.indices[h]), f"indices hop {h}"
+    if ref.features is not None:
+        assert np.array_equal(res["features"], ref.features)
+
+
+def run_one(gg, seeds_np, fanouts, key, **cap):
+    seeds = torch.from_numpy(np.ascontiguousarray(seeds_np, dtype=np.int32)).to(DEV)
+    ws = smfg.workspace_create(gg.g, len(seeds_np), fanouts)
+    out = smfg.alloc_output(gg.g, len(seeds_np), fanouts, **cap)
+    smfg.sample_mfg(gg.g, ws, seeds, fanouts, key, out)
+    return fetch(out, len(fanouts))
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    w = synth.WORKLOADS["tiny"]
+    g = synth.make_graph(w)
+    f = synth.make_features(w)
+    return w, GpuGraph(g.indptr.numpy(), g.indices.numpy(), f.numpy()), synth.make_seed_batches(w)
+
+
+def test_tiny_workload_all_batches(tiny):
+    w, gg, batches = tiny
+    for b, seeds in enumerate(batches):
+        key = synth.batch_rng_key(w, b)
+        res = run_one(gg, seeds.numpy(), w.fanouts, key)
+        ref = gg.oracle.sample_mfg(seeds.numpy(), w.fanouts, key)
+        assert_same(res, ref, len(w.fanouts))
+        check_mfg(gg.h_indptr, gg.h_indices, seeds.numpy(), w.fanouts, res["node_ids"], res["indptr"],
+                  res["indices"], res["n"], res["e"])
+
+
+def test_many_equals_single_and_is_repeatable(tiny):
+    w, gg, batches = tiny
+    L = len(w.fanouts)
+    G = len(batches)
+    wss = [smfg.workspace_create(gg.g, w.batch_size, w.fanouts) for _ in range(G)]
+    outs = [smfg.alloc_output(gg.g, w.batch_size, w.fanouts) for _ in range(G)]
+    seeds = [b.to(DEV) for b in batches]
+    keys = [synth.batch_rng_key(w, b) for b in range(G)]
+    for rep in range(2):                     # second round reuses the dirty workspaces
+        smfg.sample_mfg_many(gg.g, wss, seeds, w.fanouts, keys, outs)
+        for b in range(G):
+            ref = gg.oracle.sample_mfg(batches[b].numpy(), w.fanouts, keys[b])
+            assert_same(fetch(outs[b], L), ref, L)
+
+
+@pytest.mark.parametrize("fanouts", [(1,), (3, 1), (4, 4), (5, 8), (9,), (16, 2), (17,), (32, 3), (2, 2, 2, 2)])
+def test_fanout_group_sizes(fanouts):
+    """Every lane-group width (4, 8, 16, 32) and both branches (whole row / Floyd)."""
+    rng = np.random.default_rng(sum(fanouts))
+    adj = random_simple_graph(3000, 12, rng, hub=900)
+    adj[7] = []                                              # isolated node as a destination
+    adj = [[u for u in row if u != 7] for row in adj]
+    indptr, indices = csr_from_adj(adj)
+    feat = rng.standard_normal((3000, 8)).astype(np.float32)
+    gg = GpuGraph(indptr, indices, feat)
+    seeds = np.concatenate([[7, 0], rng.choice(np.arange(8, 3000), size=1201, replace=False)]).astype(np.int32)
+    res = run_one(gg, seeds, fanouts, 0xC0FFEE)
+    ref = gg.oracle.sample_mfg(seeds, fanouts, 0xC0FFEE)
+    assert_same(res, ref, len(fanouts))
+
+
+@pytest.mark.parametrize("dim,dtype", [(100, np.float16), (3, np.float16), (5, np.uint8), (1, np.float32),
+                                       (128, np.float16), (33, np.float32)])
+def test_gather_row_widths(dim, dtype):
+    """Row sizes that take the 16-, 8-, 4-, 2- and 1-byte vector paths."""
+    rng = np.random.default_rng(dim)
+    adj = random_simple_graph(2000, 10, rng)
+    indptr, indices = csr_from_adj(adj)
+    feat = (rng.standard_normal((2000, dim)) * 50).astype(dtype)
+    gg = GpuGraph(indptr, indices, feat)
+    seeds = rng.choice(2000, size=300, replace=False).astype(np.int32)
+    res = run_one(gg, seeds, (6, 4), 99)
+    ref = gg.oracle.sample_mfg(seeds, (6, 4), 99)
+    assert_same(res, ref, 2)
+    # stand-alone gather entry point against torch indexing
+    ids = torch.from_numpy(res["node_ids"]).to(DEV)
+    n = torch.tensor([ids.numel()], dtype=torch.int64, device=DEV)
+    out = torch.zeros((ids.numel() + 3, dim), dtype=gg.feat.dtype, device=DEV)
+    smfg.gather_rows(gg.g, ids, n, ids.numel() + 3, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:ids.numel()], gg.feat[ids.long()])
+    assert (out[ids.numel():] == 0).all()
+
+
+def test_empty_and_single_seed(tiny):
+    w, gg, _ = tiny
+    res = run_one(gg, np.zeros(0, dtype=np.int32), (3, 2), 5)
+    assert res["status"] == 0 and res["counts"] == [0, 0, 0, 0, 0, 0]
+    for v in (0, 9999):
+        res = run_one(gg, np.array([v], dtype=np.int32), (3, 2), 5)
+        assert_same(res, gg.oracle.sample_mfg(np.array([v], dtype=np.int32), (3, 2), 5), 2)
+
+
+def test_full_neighbourhood_no_rng():
+    rng = np.random.default_rng(4)
+    adj = random_simple_graph(500, 6, rng)
+    maxdeg = max(len(r) for r in adj)
+    assert maxdeg <= 32
+    indptr, indices = csr_from_adj(adj)
+    gg = GpuGraph(indptr, indices, None)
+    seeds = rng.choice(500, size=20, replace=False).astype(np.int32)
+    a = run_one(gg, seeds, (maxdeg, maxdeg), 1)
+    b = run_one(gg, seeds, (maxdeg, maxdeg), 2)
+    assert_same(a, gg.oracle.sample_mfg(seeds, (maxdeg, maxdeg), 1), 2)
+    assert np.array_equal(a["node_ids"], b["node_ids"])
+
+
+def test_device_status_codes(tiny):
+    w, gg, batches = tiny
+    s = batches[0].numpy().copy()
+    dup = s.copy(); dup[5] = dup[200]
+    assert run_one(gg, dup, (4,), 1)["status"] == smfg.ST_DUPLICATE_SEED
+    oob = s.copy(); oob[17] = gg.g.num_nodes
+    assert run_one(gg, oob, (4,), 1)["status"] == smfg.ST_SEED_OUT_OF_RANGE
+    neg = s.copy(); neg[0] = -1
+    assert run_one(gg, neg, (4,), 1)["status"] == smfg.ST_SEED_OUT_OF_RANGE
+    ref = gg.oracle.sample_mfg(s, (10, 5), 3)
+    n, e = ref.num_nodes, ref.num_edges
+    assert run_one(gg, s, (10, 5), 3, node_capacity=n[2] - 1)["status"] == smfg.ST_NODE_CAPACITY
+    assert run_one(gg, s, (10, 5), 3, node_capacity=n[1] - 1)["status"] == smfg.ST_NODE_CAPACITY
+    assert run_one(gg, s, (10, 5), 3, edge_capacity=[e[0], e[1] - 1])["status"] == smfg.ST_EDGE_CAPACITY
+    # exact capacities succeed
+    assert_same(run_one(gg, s, (10, 5), 3, node_capacity=n[2], edge_capacity=e), ref, 2)
+
+
+def test_host_argument_errors(tiny):
+    w, gg, batches = tiny
+    seeds = batches[0].to(DEV)
+    ws = smfg.workspace_create(gg.g, 256, (10, 5))
+    out = smfg.alloc_output(gg.g, 256, (10, 5))
+
+    def code(fn):
+        with pytest.raises(smfg.SmfgError) as ei:
+            fn()
+        return ei.value.code
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (0, 5), 1, out)) == smfg.ERR_BAD_FANOUT
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (33,), 1, out)) == smfg.ERR_BAD_FANOUT
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (), 1, out)) == smfg.ERR_TOO_MANY_LAYERS
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (2,) * 9, 1, out)) == smfg.ERR_TOO_MANY_LAYERS
+    big = torch.arange(257, dtype=torch.int32, device=DEV)
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, big, (10, 5), 1, out)) == smfg.ERR_TOO_MANY_SEEDS
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (10, 5, 5), 1,
+                                        smfg.alloc_output(gg.g, 256, (10, 5, 5)))) == smfg.ERR_CAPACITY
+    assert code(lambda: smfg.sample_mfg_many(gg.g, [ws, ws], [seeds, seeds], (10, 5), [1, 2], [out, out])) \
+        == smfg.ERR_INVALID_ARG
+    # a smaller request on the same workspace is fine, and the workspace is still usable
+    smfg.sample_mfg(gg.g, ws, seeds, (10,), 1, out)
+    assert fetch(out, 1)["status"] == 0
+
+
+def test_mid_workload_sampled_batches():
+    """arxiv-shaped workload: first, middle and the partial last batch, element by element."""
+    w = synth.WORKLOADS["mid"]
+    g = synth.make_graph(w)
+    f = synth.make_features(w)
+    gg = GpuGraph(g.indptr.numpy(), g.indices.numpy(), f.numpy())
+    batches = synth.make_seed_batches(w)
+    L = len(w.fanouts)
+    ws = smfg.workspace_create(gg.g, w.batch_size, w.fanouts)
+    out = smfg.alloc_output(gg.g, w.batch_size, w.fanouts)
+    for b in (0, 1, len(batches) // 2, len(batches) - 1):
+        key = synth.batch_rng_key(w, b)
+        smfg.sample_mfg(gg.g, ws, batches[b].to(DEV), w.fanouts, key, out)
+        assert_same(fetch(out, L), gg.oracle.sample_mfg(batches[b].numpy(), w.fanouts, key), L)
