@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--stages", action="store_true", help="extra untimed pass with every launch timed")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run plain copies of known size (1 GiB in, 1 GiB out) for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (batches are independent, so more GPUs would each "
@@ -182,6 +184,20 @@ def main():
         run_calls(W, K)
         st = smfg.profile_end()
         result["stage_ms_per_batch"] = {s: ms / K for s, (ms, _) in st.items()}
+
+    if args.calibrate:
+        a = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                       # plain device copy: 1 GiB read, 1 GiB written
+        rows = (1 << 30) // row_bytes
+        ids = torch.arange(rows, dtype=torch.int32, device=dev)
+        nrows = torch.tensor([rows], dtype=torch.int64, device=dev)
+        dst = b.view(torch.uint8)[:rows * row_bytes].view(feat.dtype).view(rows, -1)
+        smfg.gather_rows(g, ids, nrows, rows, dst)   # identity gather: rows * row_bytes in and out
+        torch.cuda.synchronize()
+        log(f"[calibrate] torch copy 1 GiB; identity gather of {rows} rows x {row_bytes} B")
+        del a, b
 
     if not args.no_cpu:
         import numpy as np
