@@ -92,6 +92,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="papers")
     ap.add_argument("--batches-per-call", type=int, default=8)
+    ap.add_argument("--streams", type=int, default=2,
+                    help="launch sets alternate over this many HIP streams, each with its own workspaces")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
     ap.add_argument("--no-cpu", action="store_true")
@@ -124,8 +126,10 @@ def main():
     G = max(1, min(args.batches_per_call, smfg.MAX_BATCHES))
     L = len(w.fanouts)
     g = smfg.graph_create(graph.indptr, graph.indices, feat)
-    wss = [smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(G)]
-    outs = [smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)]
+    S = max(1, args.streams)
+    streams = [torch.cuda.Stream() for _ in range(S)]
+    wss = [[smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
+    outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
     row_bytes = g.row_bytes
 
     K = max(G, (args.steps // G) * G)
@@ -136,10 +140,12 @@ def main():
 
     def run_calls(first, n):
         for c in range(first, first + n, G):
+            q = (c // G) % S
             idx = [(c + b) % len(batches) for b in range(G)]
             for b in range(G):
-                outs[b].c.counts = counts_all.data_ptr() + (c + b) * stride
-            smfg.sample_mfg_many(g, wss, [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx], outs)
+                outs[q][b].c.counts = counts_all.data_ptr() + (c + b) * stride
+            smfg.sample_mfg_many(g, wss[q], [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx],
+                                 outs[q], stream=streams[q])
 
     run_calls(0, W)
     torch.cuda.synchronize()
@@ -167,7 +173,7 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {graph.num_edges} directed edges, "
                                f"features {w.feat_dim}x{str(w.feat_dtype).split('.')[-1]}, fanouts {list(w.fanouts)}, "
-                               f"batch {w.batch_size}", "batches_per_call": G,
+                               f"batch {w.batch_size}", "batches_per_call": G, "streams": S,
                    "mean_nodes_per_batch": n_final / K, "mean_edges_per_batch": edges / K},
         "sampled_edges_per_s": edges / dt,
         "gather_GBps": gather_gbs,
@@ -203,16 +209,17 @@ def main():
         import numpy as np
 
         def gpu_check(ref, i):
-            outs[0].c.counts = counts_all.data_ptr()
-            smfg.sample_mfg(g, wss[0], batches[i], w.fanouts, keys[i], outs[0])
-            c = smfg.read_counts(outs[0])
+            o = outs[0][0]
+            o.c.counts = counts_all.data_ptr()
+            smfg.sample_mfg(g, wss[0][0], batches[i], w.fanouts, keys[i], o)
+            c = smfg.read_counts(o)
             n, e = c[:L + 1], c[L + 1:2 * L + 1]
             ok = c == [int(x) for x in ref.counts]
-            ok = ok and np.array_equal(outs[0].node_ids[:n[L]].cpu().numpy(), ref.node_ids)
+            ok = ok and np.array_equal(o.node_ids[:n[L]].cpu().numpy(), ref.node_ids)
             for h in range(L):
-                ok = ok and np.array_equal(outs[0].indptr[h][:n[h] + 1].cpu().numpy(), ref.indptr[h])
-                ok = ok and np.array_equal(outs[0].indices[h][:e[h]].cpu().numpy(), ref.indices[h])
-            got = outs[0].features[:n[L]].cpu().numpy().view(np.uint8).reshape(n[L], row_bytes)
+                ok = ok and np.array_equal(o.indptr[h][:n[h] + 1].cpu().numpy(), ref.indptr[h])
+                ok = ok and np.array_equal(o.indices[h][:e[h]].cpu().numpy(), ref.indices[h])
+            got = o.features[:n[L]].cpu().numpy().view(np.uint8).reshape(n[L], row_bytes)
             return bool(ok and np.array_equal(got, ref.features))
 
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))

@@ -161,7 +161,7 @@ int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, voi
 #define SMFG_STAGE_SAMPLE 2
 #define SMFG_STAGE_FLAG 3
 #define SMFG_STAGE_SCAN_TILES 4
-#define SMFG_STAGE_PUBLISH 5
+#define SMFG_STAGE_SCAN_ROWS 5
 #define SMFG_STAGE_ASSEMBLE 6
 #define SMFG_STAGE_GATHER 7
 #define SMFG_NUM_STAGES 8

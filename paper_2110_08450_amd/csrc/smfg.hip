@@ -1,19 +1,26 @@
 // libsmfg: sampled mini-batch preparation on gfx950 (MI355X).  Implements include/smfg.h.
 //
-// One hop h of one batch is five launches (all batches of a call share each launch through
+// One hop h of one batch is four launches (all batches of a call share each launch through
 // blockIdx.y):
 //   sample_insert  per destination: degree, Floyd/Philox row positions, neighbour ids, and an
 //                  insert of each neighbour into the batch's dedup table carrying the sample's
 //                  scan position (section 4.1 "fusing sampling and MFG construction": the edge
-//                  is recorded the moment the neighbour is picked);
-//   flag_rows      which samples are the first appearance of their node (table value == own
-//                  position), as one bit mask per destination, plus per-tile totals;
+//                  is recorded the moment the neighbour is picked).  The insert's own return
+//                  values settle everything: a known node yields its final local id; a sample
+//                  that claims a slot or lowers its value is the node's owner for now; a sample
+//                  that finds a smaller position keeps that position as a pointer; a sample that
+//                  lowers the value tells the one it displaced (`lostto`), exactly once;
+//   flag_rows      streaming, one block per tile of 256 destinations: owner samples that were
+//                  not displaced are the first appearances; one bit mask per destination, the
+//                  in-tile exclusive scan of (samples, new nodes) per destination, per-tile
+//                  totals; displaced owners turn into pointers and `lostto` is cleared again;
 //   scan_tiles     exclusive scan of the tile totals, E_h and n_{h+1};
-//   scan_publish   per-row offsets (block indptr) and ranks of new nodes; the first appearance
-//                  of a node writes its final local id into the table and its global id into
-//                  node_ids (the auto-increment of procedure OneHopMFG, made order-independent:
-//                  the id is the rank of the first appearance in (destination, slot) order);
-//   assemble       block indices = final local id of every sample.
+//   assemble       streaming, one block per tile: block indptr; final local id of every sample
+//                  -> block indices; first appearances also write node_ids and (unless this is
+//                  the last hop) the final id into the table (the auto-increment of procedure
+//                  OneHopMFG, made order-independent: the id is the rank of the first appearance
+//                  in (destination, slot) order); the other samples of a new node follow their
+//                  pointer (positions only decrease along it) to the first appearance.
 // Then one gather launch copies the feature rows of the final node list (Listing 1, xs = x[ids]).
 //
 // The dedup table is open addressing over 64-bit slots (key << 32 | value).  A known node holds
@@ -33,8 +40,10 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kTileRows = 1024;             // destinations per scan tile
-constexpr uint32_t kPend = 0x80000000u;     // value bit: position of this hop, not yet a local id
+constexpr int kTileRows = 256;              // destinations per scan tile
+constexpr uint32_t kPend = 0x80000000u;     // table value / entry tag: a position of this hop
+constexpr uint32_t kSlot = 0x40000000u;     // entry tag: index of the sample's table slot
+constexpr uint32_t kTagMask = 0xC0000000u;
 constexpr uint64_t kEmpty = ~0ull;
 
 struct BatchCtx {
@@ -42,9 +51,14 @@ struct BatchCtx {
   int64_t* counts;       // [2L+2]
   uint64_t* table;
   int32_t* node_ids;
-  int32_t* slot;         // [(destination, s)] -> table slot of that sample
+  uint32_t* ent;         // per (destination, s): final local id | kSlot+slot (owner) | kPend+position
+  uint32_t* lostto;      // per (destination, s): 0, or kPend+position of the sample that displaced it
+  int64_t lostto_entries;
+  int32_t* gsrc;         // per (destination, s): global id of the sampled neighbour
   int32_t* rowk;         // samples per destination
   uint32_t* rowmask;     // first-appearance bits per destination
+  int32_t* newrank;      // new nodes of the tile before this destination's first new node
+  int32_t* rowoff;       // samples of the tile before this destination
   uint64_t* tile_sums;   // per tile: (edges << 32 | new nodes), later their exclusive scan
   int32_t* blk_indptr;   // hop h
   int32_t* blk_indices;  // hop h
@@ -104,30 +118,34 @@ __device__ __forceinline__ uint32_t hash_slot(uint32_t key, uint32_t shift) {
   return (key * 0x9E3779B1u) >> shift;
 }
 
-// Inserts key with value `val` or lowers the stored value to `val`; returns the slot.
-// `existed` is set when the key was already there (used to detect duplicate seeds).
+// Inserts key with value `val`, or lowers the stored value to `val`.  Returns the value that
+// stood in the table just before this sample's own update took effect (0xFFFFFFFF when the key
+// was new) and the slot in `slot`.  The first access of a probe is the compare-and-swap itself:
+// on the common paths (key new, or key present with a smaller value) it is the only access.
+// If the returned value is larger than `val`, this call is the one and only update that
+// replaced exactly that value.
 __device__ __forceinline__ uint32_t table_insert_min(const BatchCtx& B, uint32_t key, uint32_t val,
-                                                     bool& existed, bool& full) {
+                                                     uint32_t& slot, bool& full) {
   unsigned long long* T = reinterpret_cast<unsigned long long*>(B.table);
   const unsigned long long mine = (static_cast<unsigned long long>(key) << 32) | val;
   uint32_t s = hash_slot(key, B.table_shift);
-  existed = false;
   full = false;
   for (uint32_t probes = 0; probes <= B.table_mask; ++probes) {
-    unsigned long long cur = __hip_atomic_load(&T[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (cur == kEmpty) {
-      cur = atomicCAS(&T[s], kEmpty, mine);
-      if (cur == kEmpty) return s;
+    unsigned long long old = atomicCAS(&T[s], kEmpty, mine);
+    if (old == kEmpty) {
+      slot = s;
+      return 0xFFFFFFFFu;
     }
-    if (static_cast<uint32_t>(cur >> 32) == key) {
-      existed = true;
-      if (static_cast<uint32_t>(cur) > val) atomicMin(&T[s], mine);
-      return s;
+    if (static_cast<uint32_t>(old >> 32) == key) {
+      slot = s;
+      if (static_cast<uint32_t>(old) > val) old = atomicMin(&T[s], mine);
+      return static_cast<uint32_t>(old);
     }
     s = (s + 1) & B.table_mask;
   }
   full = true;
-  return 0;
+  slot = 0;
+  return 0u;
 }
 
 // ---- kernels --------------------------------------------------------------------------------
@@ -153,10 +171,11 @@ __global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
       set_status(B, P.L, SMFG_ST_SEED_OUT_OF_RANGE);
       continue;
     }
-    bool existed, full;
-    table_insert_min(B, static_cast<uint32_t>(v), static_cast<uint32_t>(i), existed, full);
-    if (existed) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
+    uint32_t slot;
+    bool full;
+    const uint32_t prev = table_insert_min(B, static_cast<uint32_t>(v), static_cast<uint32_t>(i), slot, full);
     if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
+    else if (prev != 0xFFFFFFFFu) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
     B.node_ids[i] = v;
   }
 }
@@ -196,70 +215,34 @@ __global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
     }
     // Floyd's subset algorithm, resolved slot by slot: pick t_s unless an earlier slot holds it,
     // then pick j_s.  The membership test is a linear search over the lanes (the array set).
-    for (int q = 0; q < d; ++q) {
-      const uint32_t tq = __shfl(t, q, GS);
-      const bool hit = floyd && s < q && p == tq;
-      const unsigned long long bal = (__ballot(hit) >> gshift) & gmask;
-      if (floyd && s == q) p = bal ? j : tq;
+    if (__any(floyd)) {
+      for (int q = 0; q < d; ++q) {
+        const uint32_t tq = __shfl(t, q, GS);
+        const bool hit = floyd && s < q && p == tq;
+        const unsigned long long bal = (__ballot(hit) >> gshift) & gmask;
+        if (floyd && s == q) p = bal ? j : tq;
+      }
     }
     if (row && static_cast<uint32_t>(s) < k) {
       const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
       const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
-      bool existed, full;
-      const uint32_t sl = table_insert_min(B, g, kPend | pos, existed, full);
+      uint32_t slot;
+      bool full;
+      const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
       if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
-      B.slot[pos] = static_cast<int32_t>(sl);
+      // prev < kPend      : a node known before this hop, prev is its final local id
+      // prev < kPend|pos  : an earlier sample of this hop holds the node: keep it as a pointer
+      // prev > kPend|pos  : this sample now holds the node; it displaced the sample at prev
+      //                     (unless the node was new), which is told so through lostto
+      uint32_t e = prev;
+      if (prev > (kPend | pos)) {
+        e = kSlot | slot;
+        if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
+      }
+      B.ent[pos] = e;
+      B.gsrc[pos] = static_cast<int32_t>(g);
     }
     if (row && s == 0) B.rowk[i] = static_cast<int32_t>(k);
-  }
-}
-
-__device__ __forceinline__ unsigned long long block_sum(unsigned long long x, unsigned long long* lds) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) x += __shfl_down(x, o, 64);
-  const int wave = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) lds[wave] = x;
-  __syncthreads();
-  unsigned long long r = 0;
-#pragma unroll
-  for (int w = 0; w < kThreads / 64; ++w) r += lds[w];
-  return r;
-}
-
-template <int GS>
-__global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int d = P.d;
-  constexpr int kGroups = kThreads / GS;
-  const int s = threadIdx.x & (GS - 1);
-  const int grp = threadIdx.x / GS;
-  const int gshift = (threadIdx.x & 63) & ~(GS - 1);
-  const unsigned long long gmask = (GS == 64) ? ~0ull : ((1ull << GS) - 1ull);
-  const int tiles = (n + kTileRows - 1) / kTileRows;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    unsigned long long acc = 0;
-    for (int r0 = 0; r0 < kTileRows && tile * kTileRows + r0 < n; r0 += kGroups) {
-      const int i = tile * kTileRows + r0 + grp;
-      const bool row = i < n;
-      const int k = row ? B.rowk[i] : 0;
-      bool first = false;
-      if (s < k) {
-        const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
-        const uint64_t e = B.table[B.slot[pos]];
-        first = static_cast<uint32_t>(e) == (kPend | pos);
-      }
-      const uint32_t mask = static_cast<uint32_t>((__ballot(first) >> gshift) & gmask);
-      if (row && s == 0) {
-        B.rowmask[i] = mask;
-        acc += (static_cast<unsigned long long>(k) << 32) | static_cast<unsigned long long>(__popc(mask));
-      }
-    }
-    const unsigned long long tot = block_sum(acc, lds);
-    if (threadIdx.x == 0) B.tile_sums[tile] = tot;
   }
 }
 
@@ -285,6 +268,87 @@ __device__ __forceinline__ unsigned long long block_exscan(unsigned long long x,
   }
   total = tot;
   return base + inc - x;
+}
+
+// (destination, slot) of the idx-th padded sample of a tile: idx = r * d + s.
+struct DivD {
+  uint64_t inv;  // ceil(2^32 / d); the quotient is exact for idx < 2^27
+  uint32_t d;
+  __device__ __forceinline__ explicit DivD(uint32_t d_) : inv((0xFFFFFFFFull / d_) + 1ull), d(d_) {}
+  __device__ __forceinline__ void split(uint32_t idx, uint32_t& r, uint32_t& s) const {
+    r = static_cast<uint32_t>((static_cast<uint64_t>(idx) * inv) >> 32);
+    s = idx - r * d;
+  }
+};
+
+// One block per tile of kTileRows destinations.  The padded samples of a tile are one contiguous
+// span of ent / lostto, read flat and coalesced.
+__global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  __shared__ int k_lds[kTileRows];
+  __shared__ unsigned int mask_lds[kTileRows];
+  static_assert(kTileRows == kThreads, "one row per thread");
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) {
+    // a failed sample_insert may have left displacement notes behind: wipe them all
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < B.lostto_entries;
+         q += static_cast<int64_t>(gridDim.x) * kThreads)
+      B.lostto[q] = 0u;
+    return;
+  }
+  const int n = static_cast<int>(B.counts[P.h]);
+  const uint32_t d = static_cast<uint32_t>(P.d);
+  const DivD div(d);
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const int i0 = tile * kTileRows;
+    const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
+    const int tr = threadIdx.x;
+    __syncthreads();
+    k_lds[tr] = tr < nrows ? B.rowk[i0 + tr] : 0;
+    mask_lds[tr] = 0u;
+    __syncthreads();
+    const uint32_t pos0 = static_cast<uint32_t>(i0) * d;
+    const uint32_t cnt = static_cast<uint32_t>(nrows) * d;
+    constexpr int U = 4;
+    for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
+      uint32_t lost[U], e[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        lost[u] = idx < cnt ? B.lostto[pos0 + idx] : 0u;
+        e[u] = idx < cnt ? B.ent[pos0 + idx] : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        if (idx < cnt) {
+          uint32_t r, sl;
+          div.split(idx, r, sl);
+          if (sl < static_cast<uint32_t>(k_lds[r])) {
+            if (lost[u] != 0u) {  // displaced by the sample at lost[u]: follow it later
+              B.ent[pos0 + idx] = lost[u];
+              B.lostto[pos0 + idx] = 0u;
+            } else if ((e[u] & kTagMask) == kSlot) {
+              atomicOr(&mask_lds[r], 1u << sl);
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const int k = k_lds[tr];
+    const uint32_t m = mask_lds[tr];
+    const unsigned long long x = (static_cast<unsigned long long>(k) << 32) | static_cast<unsigned long long>(__popc(m));
+    unsigned long long total;
+    const unsigned long long pre = block_exscan(x, lds, total);
+    if (tr < nrows) {
+      B.rowmask[i0 + tr] = m;
+      B.rowoff[i0 + tr] = static_cast<int32_t>(pre >> 32);
+      B.newrank[i0 + tr] = static_cast<int32_t>(pre & 0xFFFFFFFFull);
+    }
+    if (tr == 0) B.tile_sums[tile] = total;
+  }
 }
 
 __global__ void __launch_bounds__(kThreads) k_scan_tiles(const Launch P) {
@@ -313,98 +377,115 @@ __global__ void __launch_bounds__(kThreads) k_scan_tiles(const Launch P) {
   }
 }
 
-// One thread per 4 consecutive destinations of a tile.
-__global__ void __launch_bounds__(kThreads) k_scan_publish(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
+// One block per tile of kTileRows destinations; samples are walked flat like in k_flag_rows.
+__global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
+  __shared__ int k_lds[kTileRows];
+  __shared__ unsigned int mask_lds[kTileRows];
+  __shared__ unsigned int off_lds[kTileRows];   // global edge offset of the destination
+  __shared__ unsigned int rank_lds[kTileRows];  // local id of the destination's first new node
   const BatchCtx& B = P.b[blockIdx.y];
   if (status_of(B, P.L) != 0) return;
   const int n = static_cast<int>(B.counts[P.h]);
-  const int d = P.d;
+  const uint32_t d = static_cast<uint32_t>(P.d);
+  const DivD div(d);
+  const bool last = P.h == P.L - 1;  // nodes found in the last hop are never looked up again
   const int tiles = (n + kTileRows - 1) / kTileRows;
-  static_assert(kTileRows == 4 * kThreads, "four rows per thread");
   for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const int i0 = tile * kTileRows + threadIdx.x * 4;
-    int k[4];
-    uint32_t m[4];
-    unsigned long long mine = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const bool row = i0 + r < n;
-      k[r] = row ? B.rowk[i0 + r] : 0;
-      m[r] = row ? B.rowmask[i0 + r] : 0u;
-      mine += (static_cast<unsigned long long>(k[r]) << 32) | static_cast<unsigned long long>(__popc(m[r]));
-    }
-    unsigned long long total;
-    unsigned long long pre = B.tile_sums[tile] + block_exscan(mine, lds, total);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int i = i0 + r;
-      if (i < n) {
-        B.blk_indptr[i] = static_cast<int32_t>(pre >> 32);
-        uint32_t local = static_cast<uint32_t>(n) + static_cast<uint32_t>(pre & 0xFFFFFFFFull);
-        uint32_t bits = m[r];
-        while (bits) {
-          const int sbit = __ffs(bits) - 1;
-          bits &= bits - 1;
-          const int32_t sl = B.slot[static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(sbit)];
-          const uint32_t key = static_cast<uint32_t>(B.table[sl] >> 32);
-          B.table[sl] = (static_cast<uint64_t>(key) << 32) | local;
-          B.node_ids[local] = static_cast<int32_t>(key);
-          ++local;
-        }
-      }
-      pre += (static_cast<unsigned long long>(k[r]) << 32) | static_cast<unsigned long long>(__popc(m[r]));
+    const int i0 = tile * kTileRows;
+    const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
+    const int tr = threadIdx.x;
+    const unsigned long long tpre = B.tile_sums[tile];
+    __syncthreads();
+    if (tr < nrows) {
+      const uint32_t off = static_cast<uint32_t>(tpre >> 32) + static_cast<uint32_t>(B.rowoff[i0 + tr]);
+      k_lds[tr] = B.rowk[i0 + tr];
+      mask_lds[tr] = B.rowmask[i0 + tr];
+      off_lds[tr] = off;
+      rank_lds[tr] = static_cast<uint32_t>(n) + static_cast<uint32_t>(tpre & 0xFFFFFFFFull) +
+                     static_cast<uint32_t>(B.newrank[i0 + tr]);
+      B.blk_indptr[i0 + tr] = static_cast<int32_t>(off);
+    } else {
+      k_lds[tr] = 0;
     }
     __syncthreads();
-  }
-}
-
-template <int GS>
-__global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int d = P.d;
-  constexpr int kGroups = kThreads / GS;
-  const int s = threadIdx.x & (GS - 1);
-  const int grp = threadIdx.x / GS;
-  for (int i = blockIdx.x * kGroups + grp; i < n; i += gridDim.x * kGroups) {
-    const int k = B.rowk[i];
-    if (s < k) {
-      const int32_t base = B.blk_indptr[i];
-      const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
-      B.blk_indices[base + s] = static_cast<int32_t>(static_cast<uint32_t>(B.table[B.slot[pos]]));
+    const uint32_t pos0 = static_cast<uint32_t>(i0) * d;
+    const uint32_t cnt = static_cast<uint32_t>(nrows) * d;
+    constexpr int U = 4;
+    for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
+      uint32_t e[U], g[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        e[u] = idx < cnt ? B.ent[pos0 + idx] : 0u;
+        g[u] = idx < cnt ? static_cast<uint32_t>(B.gsrc[pos0 + idx]) : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        if (idx >= cnt) continue;
+        uint32_t r, sl;
+        div.split(idx, r, sl);
+        if (sl >= static_cast<uint32_t>(k_lds[r])) continue;
+        const uint32_t tag = e[u] & kTagMask;
+        uint32_t local = e[u];
+        if (tag == kSlot) {  // first appearance: rank among the new nodes of this hop
+          local = rank_lds[r] + __popc(mask_lds[r] & ((1u << sl) - 1u));
+          B.node_ids[local] = static_cast<int32_t>(g[u]);
+          if (!last) B.table[e[u] & ~kTagMask] = (static_cast<uint64_t>(g[u]) << 32) | local;
+        } else if (tag != 0u) {  // kPend: same node as the sample at position q < own position
+          uint32_t q = e[u] & ~kTagMask;
+          for (;;) {
+            const uint32_t qi = q / d, qs = q - qi * d;
+            const uint32_t m = B.rowmask[qi];
+            if ((m >> qs) & 1u) {  // q is the node's first appearance
+              local = static_cast<uint32_t>(n) +
+                      static_cast<uint32_t>(B.tile_sums[qi / kTileRows] & 0xFFFFFFFFull) +
+                      static_cast<uint32_t>(B.newrank[qi]) + __popc(m & ((1u << qs) - 1u));
+              break;
+            }
+            const uint32_t nxt = B.ent[q] & ~kTagMask;  // strictly smaller position
+            if (nxt >= q) break;                        // cannot happen; guards the loop
+            q = nxt;
+          }
+        }
+        B.blk_indices[off_lds[r] + sl] = static_cast<int32_t>(local);
+      }
     }
   }
 }
 
-// Rows are moved as vectors of VEC bytes; the output is addressed as one flat vector array so
-// stores are fully coalesced, and the lanes that share a row read one contiguous span of it.
+// Rows are moved as vectors of sizeof(V) bytes.  A block copies kGatherRows consecutive output
+// rows and exits: many short-lived blocks reach a higher copy rate on this chip than a persistent
+// grid-stride loop.  Inside a block the output chunk is addressed as one flat vector array, so
+// stores are fully coalesced and the lanes that share a row read one contiguous span of it.
+constexpr int kGatherRows = 32;
 template <typename V>
 __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, int64_t row_stride,
                                             uint32_t vec_per_row, const int32_t* __restrict__ ids,
                                             int64_t n, uint8_t* __restrict__ out) {
   constexpr int U = 4;
-  const uint64_t total = static_cast<uint64_t>(n) * vec_per_row;
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * kThreads;
-  V* __restrict__ o = reinterpret_cast<V*>(out);
-  for (uint64_t base = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x; base < total;
-       base += stride * U) {
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
+  if (r0 >= n) return;
+  const uint32_t rows = static_cast<uint32_t>(n - r0 < kGatherRows ? n - r0 : kGatherRows);
+  const uint32_t cnt = rows * vec_per_row;
+  const int32_t* __restrict__ id0 = ids + r0;
+  V* __restrict__ o = reinterpret_cast<V*>(out) + static_cast<uint64_t>(r0) * vec_per_row;
+  for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
     V val[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const uint64_t idx = base + static_cast<uint64_t>(u) * stride;
-      if (idx < total) {
-        const uint32_t jrow = static_cast<uint32_t>(idx / vec_per_row);
-        const uint32_t c = static_cast<uint32_t>(idx - static_cast<uint64_t>(jrow) * vec_per_row);
-        const V* src = reinterpret_cast<const V*>(feat + static_cast<int64_t>(ids[jrow]) * row_stride);
+      const uint32_t idx = base + u * kThreads;
+      if (idx < cnt) {
+        const uint32_t jrow = idx / vec_per_row;
+        const uint32_t c = idx - jrow * vec_per_row;
+        const V* src = reinterpret_cast<const V*>(feat + static_cast<int64_t>(id0[jrow]) * row_stride);
         val[u] = __builtin_nontemporal_load(src + c);
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const uint64_t idx = base + static_cast<uint64_t>(u) * stride;
-      if (idx < total) __builtin_nontemporal_store(val[u], o + idx);
+      const uint32_t idx = base + u * kThreads;
+      if (idx < cnt) __builtin_nontemporal_store(val[u], o + idx);
     }
   }
 }
@@ -508,9 +589,13 @@ struct smfg_workspace {
   uint32_t table_log2;
   void* slab;
   uint64_t* table;
-  int32_t* slot;
+  uint32_t* ent;
+  uint32_t* lostto;
+  int32_t* gsrc;
   int32_t* rowk;
   uint32_t* rowmask;
+  int32_t* newrank;
+  int32_t* rowoff;
   uint64_t* tile_sums;
 };
 
@@ -618,7 +703,7 @@ int smfg_workspace_create(smfg_workspace_t** out, const smfg_graph_t* g, int32_t
   if (node_capacity < 1) node_capacity = 1;
   if (node_capacity < mn[0]) return SMFG_ERR_TOO_MANY_SEEDS;
   const int64_t slots = slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity);
-  if (slots >= (1ll << 31) || node_capacity >= (1ll << 30)) return SMFG_ERR_CAPACITY;
+  if (slots >= (1ll << 30) || node_capacity > (1ll << 29)) return SMFG_ERR_CAPACITY;
 
   uint32_t lg = 10;
   while ((1ll << lg) < 2 * node_capacity) ++lg;
@@ -641,23 +726,36 @@ int smfg_workspace_create(smfg_workspace_t** out, const smfg_graph_t* g, int32_t
   const int64_t b_rowk = align((node_capacity + 4) * 4);
   const int64_t b_mask = align((node_capacity + 4) * 4);
   const int64_t b_tiles = align(tiles * 8);
-  ws->bytes = b_table + b_slot + b_rowk + b_mask + b_tiles;
+  ws->bytes = b_table + 3 * b_slot + 4 * b_rowk + b_tiles;
   int cur = 0;
   (void)hipGetDevice(&cur);
   if (cur != g->device) (void)hipSetDevice(g->device);
   hipError_t e = hipMalloc(&ws->slab, static_cast<size_t>(ws->bytes));
-  if (cur != g->device) (void)hipSetDevice(cur);
   if (e != hipSuccess) {
     (void)hipGetLastError();
+    if (cur != g->device) (void)hipSetDevice(cur);
     delete ws;
     return SMFG_ERR_OOM;
   }
   uint8_t* p = static_cast<uint8_t*>(ws->slab);
   ws->table = reinterpret_cast<uint64_t*>(p); p += b_table;
-  ws->slot = reinterpret_cast<int32_t*>(p); p += b_slot;
+  ws->ent = reinterpret_cast<uint32_t*>(p); p += b_slot;
+  ws->lostto = reinterpret_cast<uint32_t*>(p); p += b_slot;
+  ws->gsrc = reinterpret_cast<int32_t*>(p); p += b_slot;
   ws->rowk = reinterpret_cast<int32_t*>(p); p += b_rowk;
   ws->rowmask = reinterpret_cast<uint32_t*>(p); p += b_mask;
+  ws->newrank = reinterpret_cast<int32_t*>(p); p += b_rowk;
+  ws->rowoff = reinterpret_cast<int32_t*>(p); p += b_rowk;
   ws->tile_sums = reinterpret_cast<uint64_t*>(p);
+  // displacement notes start out clear; flag_rows clears whatever a call writes
+  e = hipMemset(ws->lostto, 0, static_cast<size_t>(b_slot));
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (cur != g->device) (void)hipSetDevice(cur);
+  if (e != hipSuccess) {
+    (void)hipFree(ws->slab);
+    delete ws;
+    return hip_err(e);
+  }
   *out = ws;
   return SMFG_OK;
 }
@@ -731,9 +829,14 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     B.counts = o.counts;
     B.table = w->table;
     B.node_ids = o.node_ids;
-    B.slot = w->slot;
+    B.ent = w->ent;
+    B.lostto = w->lostto;
+    B.lostto_entries = w->slot_entries;
+    B.gsrc = w->gsrc;
     B.rowk = w->rowk;
     B.rowmask = w->rowmask;
+    B.newrank = w->newrank;
+    B.rowoff = w->rowoff;
     B.tile_sums = w->tile_sums;
     B.features = static_cast<uint8_t*>(o.features);
     B.node_capacity = static_cast<int32_t>(o.node_capacity);
@@ -780,31 +883,24 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     const unsigned row_blocks = blocks_for(rows, kThreads / gs, kCap);
     const unsigned tile_blocks = blocks_for(rows, kTileRows, kCap);
     launch_by_group(gs, [&](auto GS) {
-      {
-        StageTimer t_(SMFG_STAGE_SAMPLE, st);
-        k_sample_insert<decltype(GS)::value><<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
-      }
-      {
-        StageTimer t_(SMFG_STAGE_FLAG, st);
-        k_flag_rows<decltype(GS)::value><<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
-      }
+      StageTimer t_(SMFG_STAGE_SAMPLE, st);
+      k_sample_insert<decltype(GS)::value><<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
     });
+    {
+      StageTimer t_(SMFG_STAGE_FLAG, st);
+      k_flag_rows<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
+    }
     {
       StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
       k_scan_tiles<<<dim3(1, G), kThreads, 0, st>>>(P);
     }
     {
-      StageTimer t_(SMFG_STAGE_PUBLISH, st);
-      k_scan_publish<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
-    }
-    launch_by_group(gs, [&](auto GS) {
       StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
-      k_assemble<decltype(GS)::value><<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
-    });
+      k_assemble<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
+    }
   }
   if (want_feat) {
-    const int64_t vecs = max_n[L] * (g->row_bytes / vb);
-    const unsigned gb = blocks_for(vecs, kThreads * 4, 8192);
+    const unsigned gb = blocks_for(max_n[L], kGatherRows, 0x7FFFFFFFu);
     StageTimer t_(SMFG_STAGE_GATHER, st);
     switch (vb) {
       case 16: k_gather<u32x4><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
@@ -835,7 +931,7 @@ int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int vb = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(d_out), g->row_bytes,
                            g->row_stride);
-  const unsigned gb = blocks_for(max_rows * (g->row_bytes / vb), kThreads * 4, 8192);
+  const unsigned gb = blocks_for(max_rows, kGatherRows, 0x7FFFFFFFu);
   uint8_t* o = static_cast<uint8_t*>(d_out);
   int cur = 0;
   (void)hipGetDevice(&cur);
