@@ -44,7 +44,7 @@ extern "C" {
 
 #define SMFG_MAX_LAYERS 8
 #define SMFG_MAX_FANOUT 32
-#define SMFG_MAX_BATCHES 8 /* batches per smfg_sample_mfg_many call */
+#define SMFG_MAX_BATCHES 16 /* batches per smfg_sample_mfg_many call */
 
 /* host-detected errors (return values) */
 #define SMFG_OK 0

@@ -16,7 +16,7 @@ import torch
 
 MAX_LAYERS = 8
 MAX_FANOUT = 32
-MAX_BATCHES = 8
+MAX_BATCHES = 16
 
 OK = 0
 ERR_INVALID_ARG, ERR_NULL_PTR, ERR_BAD_FANOUT, ERR_TOO_MANY_LAYERS = -1, -2, -3, -4

@@ -33,7 +33,6 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
-#include <type_traits>
 
 #include "smfg.h"
 
@@ -180,22 +179,26 @@ __global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
   }
 }
 
-// GS lanes cooperate on one destination; lane s owns slot s.
-template <int GS>
+// d lanes cooperate on one destination, lane s of the group owns slot s; a wave holds
+// floor(64 / d) groups (its last 64 mod d lanes idle).
 __global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
   const BatchCtx& B = P.b[blockIdx.y];
   if (status_of(B, P.L) != 0) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const int d = P.d;
-  constexpr int kGroups = kThreads / GS;
-  const int s = threadIdx.x & (GS - 1);
-  const int grp = threadIdx.x / GS;
-  const int gshift = (threadIdx.x & 63) & ~(GS - 1);
-  const unsigned long long gmask = (GS == 64) ? ~0ull : ((1ull << GS) - 1ull);
+  const int lane = threadIdx.x & 63;
+  const int per_wave = 64 / d;                 // destinations per wave
+  const int per_block = per_wave * (kThreads / 64);
+  const int grp = lane / d;
+  const int s = lane - grp * d;
+  const bool lane_used = grp < per_wave;
+  const int gbase = grp * d;                   // first lane of the group within the wave
+  const unsigned long long gmask = (1ull << d) - 1ull;
+  const int row_in_block = (threadIdx.x >> 6) * per_wave + grp;
 
-  for (int i0 = blockIdx.x * kGroups; i0 < n; i0 += gridDim.x * kGroups) {
-    const int i = i0 + grp;
-    const bool row = i < n;
+  for (int i0 = blockIdx.x * per_block; i0 < n; i0 += gridDim.x * per_block) {
+    const int i = i0 + row_in_block;
+    const bool row = lane_used && i < n;
     uint32_t v = 0, deg = 0;
     int64_t a = 0;
     if (row) {
@@ -207,7 +210,7 @@ __global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
     const uint32_t k = floyd ? static_cast<uint32_t>(d) : deg;
     uint32_t p = static_cast<uint32_t>(s);  // whole row in CSR order when deg <= d
     uint32_t t = 0, j = 0;
-    if (floyd && s < d) {
+    if (floyd) {
       const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), static_cast<uint32_t>(s) >> 2,
                                      B.key0, B.key1, static_cast<uint32_t>(s) & 3u);
       j = deg - static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
@@ -217,9 +220,9 @@ __global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
     // then pick j_s.  The membership test is a linear search over the lanes (the array set).
     if (__any(floyd)) {
       for (int q = 0; q < d; ++q) {
-        const uint32_t tq = __shfl(t, q, GS);
+        const uint32_t tq = __shfl(t, gbase + q, 64);
         const bool hit = floyd && s < q && p == tq;
-        const unsigned long long bal = (__ballot(hit) >> gshift) & gmask;
+        const unsigned long long bal = (__ballot(hit) >> gbase) & gmask;
         if (floyd && s == q) p = bal ? j : tq;
       }
     }
@@ -516,7 +519,6 @@ __global__ void __launch_bounds__(kThreads) k_gather_plain(const uint8_t* feat, 
 
 inline int hip_err(hipError_t e) { return e == hipSuccess ? SMFG_OK : SMFG_ERR_HIP_BASE - static_cast<int>(e); }
 
-inline int group_size(int d) { return d <= 4 ? 4 : d <= 8 ? 8 : d <= 16 ? 16 : 32; }
 
 inline int vec_bytes(uintptr_t a, uintptr_t b, int64_t row_bytes, int64_t row_stride) {
   const uint64_t x = static_cast<uint64_t>(a) | static_cast<uint64_t>(b) | static_cast<uint64_t>(row_bytes) |
@@ -621,16 +623,6 @@ int check_fanouts(int32_t L, const int32_t* fanouts) {
   for (int h = 0; h < L; ++h)
     if (fanouts[h] < 1 || fanouts[h] > SMFG_MAX_FANOUT) return SMFG_ERR_BAD_FANOUT;
   return SMFG_OK;
-}
-
-template <typename F>
-void launch_by_group(int gs, F&& f) {
-  switch (gs) {
-    case 4: f(std::integral_constant<int, 4>()); break;
-    case 8: f(std::integral_constant<int, 8>()); break;
-    case 16: f(std::integral_constant<int, 16>()); break;
-    default: f(std::integral_constant<int, 32>()); break;
-  }
 }
 
 }  // namespace
@@ -878,14 +870,13 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       P.b[b].blk_indices = outs[b].indices[h];
       P.b[b].edge_capacity = outs[b].edge_capacity[h];
     }
-    const int gs = group_size(P.d);
     const int64_t rows = max_n[h];
-    const unsigned row_blocks = blocks_for(rows, kThreads / gs, kCap);
+    const unsigned row_blocks = blocks_for(rows, (64 / P.d) * (kThreads / 64), kCap);
     const unsigned tile_blocks = blocks_for(rows, kTileRows, kCap);
-    launch_by_group(gs, [&](auto GS) {
+    {
       StageTimer t_(SMFG_STAGE_SAMPLE, st);
-      k_sample_insert<decltype(GS)::value><<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
-    });
+      k_sample_insert<<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
+    }
     {
       StageTimer t_(SMFG_STAGE_FLAG, st);
       k_flag_rows<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
