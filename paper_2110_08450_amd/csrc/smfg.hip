@@ -466,30 +466,35 @@ template <typename V>
 __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, int64_t row_stride,
                                             uint32_t vec_per_row, const int32_t* __restrict__ ids,
                                             int64_t n, uint8_t* __restrict__ out) {
-  constexpr int U = 4;
+  constexpr int U = 2;
+  __shared__ int64_t row_byte[kGatherRows];  // byte offset of each source row
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
   if (r0 >= n) return;
   const uint32_t rows = static_cast<uint32_t>(n - r0 < kGatherRows ? n - r0 : kGatherRows);
   const uint32_t cnt = rows * vec_per_row;
-  const int32_t* __restrict__ id0 = ids + r0;
+  if (threadIdx.x < kGatherRows)
+    row_byte[threadIdx.x] = threadIdx.x < rows ? static_cast<int64_t>(ids[r0 + threadIdx.x]) * row_stride : 0;
+  __syncthreads();
   V* __restrict__ o = reinterpret_cast<V*>(out) + static_cast<uint64_t>(r0) * vec_per_row;
-  for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
+  uint32_t base = threadIdx.x;
+  // full rounds: U independent row reads in flight per thread, then the U stores
+  for (; base + (U - 1) * kThreads < cnt; base += kThreads * U) {
     V val[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t idx = base + u * kThreads;
-      if (idx < cnt) {
-        const uint32_t jrow = idx / vec_per_row;
-        const uint32_t c = idx - jrow * vec_per_row;
-        const V* src = reinterpret_cast<const V*>(feat + static_cast<int64_t>(id0[jrow]) * row_stride);
-        val[u] = __builtin_nontemporal_load(src + c);
-      }
+      const uint32_t jrow = idx / vec_per_row;
+      const uint32_t c = idx - jrow * vec_per_row;
+      val[u] = __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t idx = base + u * kThreads;
-      if (idx < cnt) __builtin_nontemporal_store(val[u], o + idx);
-    }
+    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(val[u], o + base + u * kThreads);
+  }
+  for (; base < cnt; base += kThreads) {
+    const uint32_t jrow = base / vec_per_row;
+    const uint32_t c = base - jrow * vec_per_row;
+    __builtin_nontemporal_store(
+        __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c), o + base);
   }
 }
 
