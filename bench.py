@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
+# HBM bytes per k_gather launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (profiles/papers_kernel_trace_and_hbm_traffic.txt), scaled by what the same counters read
+# for the identity copy of known size; keyed by (workload, batches per launch).
+MEASURED_GATHER_TRAFFIC_BYTES = {("papers", 8): 3.613e9}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -92,7 +97,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="papers")
     ap.add_argument("--batches-per-call", type=int, default=8)
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=1,
                     help="launch sets alternate over this many HIP streams, each with its own workspaces")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
@@ -180,7 +185,8 @@ def main():
         "path_algorithmic_GBps": alg / dt / 1e9,
         "path_frac_of_hbm_peak": alg / dt / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
+                     "traffic": MEASURED_GATHER_TRAFFIC_BYTES.get((w.name, G)), "traffic_unit": "bytes per launch",
                      "avg_launch_ms": gather_ms / max(1, gather_launches),
                      "algorithmic_bytes_per_launch": gather_bytes / max(1, gather_launches)},
     }
