@@ -1,0 +1,82 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times
+(several batches per launch set), against the oracle element by element (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2110_08450_amd import binding as smfg
+from paper_2110_08450_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _check_batches(w, graph, feat, g, orc, batches, batch_ids, per_call):
+    """Runs the chosen batches `per_call` at a time and compares every output array.  The feature
+    rows are checked against torch indexing of the same table with the oracle's node list."""
+    L = len(w.fanouts)
+    wss = [smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(per_call)]
+    outs = [smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(per_call)]
+    for c0 in range(0, len(batch_ids), per_call):
+        ids = batch_ids[c0:c0 + per_call]
+        keys = [synth.batch_rng_key(w, b) for b in ids]
+        k = len(ids)
+        smfg.sample_mfg_many(g, wss[:k], [batches[b] for b in ids], w.fanouts, keys, outs[:k])
+        for q, b in enumerate(ids):
+            c = smfg.read_counts(outs[q])
+            ref = orc.sample_mfg(batches[b].cpu().numpy(), w.fanouts, keys[q], with_features=False)
+            assert ref.status == 0
+            assert c == [int(x) for x in ref.counts], f"batch {b}"
+            n, e = c[:L + 1], c[L + 1:2 * L + 1]
+            assert np.array_equal(outs[q].node_ids[:n[L]].cpu().numpy(), ref.node_ids), f"batch {b}"
+            for h in range(L):
+                assert np.array_equal(outs[q].indptr[h][:n[h] + 1].cpu().numpy(), ref.indptr[h]), (b, h)
+                assert np.array_equal(outs[q].indices[h][:e[h]].cpu().numpy(), ref.indices[h]), (b, h)
+            ids_ref = torch.from_numpy(ref.node_ids).to(DEV).long()
+            assert torch.equal(outs[q].features[:n[L]], feat[ids_ref]), f"features of batch {b}"
+            print(f"{w.name} batch {b}: nodes {n} edges {e} ok", flush=True)
+
+
+def test_large_workload_first_pass_batches():
+    """products-shaped workload (fp16 x 100: 200-byte rows), 8 batches per launch set."""
+    w = synth.WORKLOADS["large"]
+    graph = synth.make_graph(w, device=DEV)
+    feat = synth.make_features(w, device=DEV)
+    batches = synth.make_seed_batches(w, device=DEV)
+    g = smfg.graph_create(graph.indptr, graph.indices, feat)
+    orc = oracle.Oracle(graph.indptr.cpu().numpy(), graph.indices.cpu().numpy())
+    ids = list(range(8)) + [len(batches) // 2, len(batches) - 1]
+    _check_batches(w, graph, feat, g, orc, batches, ids, 8)
+
+
+@pytest.fixture(scope="module")
+def papers():
+    w = synth.WORKLOADS["papers"]
+    graph = synth.make_graph(w, device=DEV)
+    feat = synth.make_features(w, device=DEV)
+    torch.cuda.empty_cache()
+    g = smfg.graph_create(graph.indptr, graph.indices, feat)
+    orc = oracle.Oracle(graph.indptr.cpu().numpy(), graph.indices.cpu().numpy())
+    print(f"papers graph: {graph.num_edges} directed edges", flush=True)
+    return graph, feat, g, orc
+
+
+def test_papers_workload_batches(papers):
+    """papers100M-shaped workload (111 M nodes, 3.2 B edges, int64 offsets beyond 2^31), training
+    fanouts, 8 batches per launch set; first eight batches and the partial last one."""
+    graph, feat, g, orc = papers
+    w = synth.WORKLOADS["papers"]
+    assert graph.num_edges > 2**31
+    batches = synth.make_seed_batches(w, device=DEV)
+    assert batches[-1].numel() < w.batch_size
+    _check_batches(w, graph, feat, g, orc, batches, list(range(8)) + [len(batches) - 1], 8)
+
+
+def test_papers_inference_shaped_batches(papers):
+    """Same graph, fanouts (20,20,20), 4096 seeds from the held-out split: about 20 M nodes and
+    26 M edges per batch (the dedup table's largest load)."""
+    graph, feat, g, orc = papers
+    w = synth.WORKLOADS["papers_infer"]
+    batches = synth.make_seed_batches(w, device=DEV)
+    _check_batches(w, graph, feat, g, orc, batches, [0, len(batches) - 1], 2)

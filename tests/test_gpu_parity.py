@@ -93,7 +93,8 @@ def test_many_equals_single_and_is_repeatable(tiny):
             assert_same(fetch(outs[b], L), ref, L)
 
 
-@pytest.mark.parametrize("fanouts", [(1,), (3, 1), (4, 4), (5, 8), (9,), (16, 2), (17,), (32, 3), (2, 2, 2, 2)])
+@pytest.mark.parametrize("fanouts", [(1,), (3, 1), (4, 4), (5, 8), (9,), (16, 2), (17,), (32, 3), (2, 2, 2, 2),
+                                     (7, 6), (21, 13), (32, 32), (2,) * 8])
 def test_fanout_group_sizes(fanouts):
     """Every lane-group width (4, 8, 16, 32) and both branches (whole row / Floyd)."""
     rng = np.random.default_rng(sum(fanouts))
@@ -130,6 +131,21 @@ def test_gather_row_widths(dim, dtype):
     torch.cuda.synchronize()
     assert torch.equal(out[:ids.numel()], gg.feat[ids.long()])
     assert (out[ids.numel():] == 0).all()
+
+
+def test_ragged_batches_in_one_call(tiny):
+    """16 batches of different sizes (including an empty one) in one launch set."""
+    w, gg, batches = tiny
+    rng = np.random.default_rng(8)
+    sizes = [0, 1, 2, 63, 64, 65, 255, 256, 100, 17, 200, 31, 128, 5, 250, 77]
+    seeds = [rng.choice(gg.g.num_nodes, size=k, replace=False).astype(np.int32) for k in sizes]
+    fan = (6, 11, 3)
+    wss = [smfg.workspace_create(gg.g, 256, fan) for _ in sizes]
+    outs = [smfg.alloc_output(gg.g, 256, fan) for _ in sizes]
+    keys = [1000 + i for i in range(len(sizes))]
+    smfg.sample_mfg_many(gg.g, wss, [torch.from_numpy(s).to(DEV) for s in seeds], fan, keys, outs)
+    for i in range(len(sizes)):
+        assert_same(fetch(outs[i], 3), gg.oracle.sample_mfg(seeds[i], fan, keys[i]), 3)
 
 
 def test_empty_and_single_seed(tiny):
