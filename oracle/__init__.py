@@ -27,10 +27,9 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def _load():
-    global _lib
-    if _lib is None:
-        lib = ctypes.CDLL(build())
+def _configure(lib):
+    """Declares the argument types of the oracle's exports on a loaded library."""
+    if True:
         u32p = ctypes.POINTER(ctypes.c_uint32)
         lib.oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
         lib.oracle_philox4x32_10.restype = None
@@ -48,7 +47,13 @@ def _load():
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p]
-        _lib = lib
+    return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = _configure(ctypes.CDLL(build()))
     return _lib
 
 

@@ -40,22 +40,35 @@ int main(int argc, char** argv) {
 """
 
 
-@pytest.fixture(scope="module")
-def torch_philox(tmp_path_factory):
+_driver_exe = None
+
+
+def philox_driver():
+    """Compiles (once) the little program around PyTorch's engine; returns run(cases) -> words."""
+    global _driver_exe
+    import tempfile
     import torch
     inc = os.path.join(os.path.dirname(torch.__file__), "include")
     if not os.path.exists(os.path.join(inc, "ATen/core/PhiloxRNGEngine.h")):
         pytest.skip("PyTorch Philox header not shipped")
-    d = tmp_path_factory.mktemp("philox")
-    src, exe = d / "drv.cpp", d / "drv"
-    src.write_text(_DRIVER)
-    subprocess.check_call(["g++", "-O1", "-std=c++17", "-I", inc, str(src), "-o", str(exe)])
+    if _driver_exe is None:
+        d = tempfile.mkdtemp(prefix="philox_pin_")
+        src, exe = os.path.join(d, "drv.cpp"), os.path.join(d, "drv")
+        with open(src, "w") as f:
+            f.write(_DRIVER)
+        subprocess.check_call(["g++", "-O1", "-std=c++17", "-I", inc, src, "-o", exe])
+        _driver_exe = exe
 
     def run(cases):
         args = [str(x) for c in cases for x in c]
-        out = subprocess.check_output([str(exe)] + args, text=True)
+        out = subprocess.check_output([_driver_exe] + args, text=True)
         return [[int(t) for t in line.split()] for line in out.strip().splitlines()]
     return run
+
+
+@pytest.fixture(scope="module")
+def torch_philox():
+    return philox_driver()
 
 
 def test_philox_matches_library_engine(torch_philox):
