@@ -44,6 +44,7 @@ constexpr uint32_t kPend = 0x80000000u;     // table value / entry tag: a positi
 constexpr uint32_t kSlot = 0x40000000u;     // entry tag: index of the sample's table slot
 constexpr uint32_t kTagMask = 0xC0000000u;
 constexpr uint64_t kEmpty = ~0ull;
+constexpr uint32_t kMaxProbes = 4096;      // longest probe run before the table counts as full
 
 struct BatchCtx {
   const int32_t* seeds;
@@ -129,7 +130,10 @@ __device__ __forceinline__ uint32_t table_insert_min(const BatchCtx& B, uint32_t
   const unsigned long long mine = (static_cast<unsigned long long>(key) << 32) | val;
   uint32_t s = hash_slot(key, B.table_shift);
   full = false;
-  for (uint32_t probes = 0; probes <= B.table_mask; ++probes) {
+  // The table has at least two slots per node of capacity, so a probe run this long only occurs
+  // when far more distinct nodes arrive than the capacity allows: report the table as full.
+  const uint32_t max_probes = B.table_mask < kMaxProbes ? B.table_mask + 1u : kMaxProbes;
+  for (uint32_t probes = 0; probes < max_probes; ++probes) {
     unsigned long long old = atomicCAS(&T[s], kEmpty, mine);
     if (old == kEmpty) {
       slot = s;

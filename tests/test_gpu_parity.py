@@ -189,6 +189,24 @@ def test_device_status_codes(tiny):
     assert_same(run_one(gg, s, (10, 5), 3, node_capacity=n[2], edge_capacity=e), ref, 2)
 
 
+def test_overloaded_workspace_reports_and_recovers(tiny):
+    """Far more distinct nodes than the workspace was sized for: the call ends with a status
+    (table full or node capacity), and the same workspace then serves a small batch correctly."""
+    w, gg, batches = tiny
+    fan = (10, 5)
+    ws = smfg.workspace_create(gg.g, 256, fan, node_capacity=300)
+    out = smfg.alloc_output(gg.g, 256, fan, node_capacity=300)
+    for rep in range(2):
+        smfg.sample_mfg(gg.g, ws, batches[rep].to(DEV), fan, 7 + rep, out)
+        st = fetch(out, 2)["status"]
+        assert st in (smfg.ST_TABLE_FULL, smfg.ST_NODE_CAPACITY)
+        small = batches[2][:12].contiguous()
+        smfg.sample_mfg(gg.g, ws, small.to(DEV), (3, 2), 11, out)
+        ref = gg.oracle.sample_mfg(small.numpy(), (3, 2), 11)
+        assert ref.num_nodes[-1] <= 300
+        assert_same(fetch(out, 2), ref, 2)
+
+
 def test_host_argument_errors(tiny):
     w, gg, batches = tiny
     seeds = batches[0].to(DEV)
