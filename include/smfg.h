@@ -145,6 +145,16 @@ int smfg_sample_mfg_many(const smfg_graph_t *g, smfg_workspace_t *const *ws,
 int smfg_gather_rows(const smfg_graph_t *g, const int32_t *d_node_ids, const int64_t *d_num_rows,
                      int64_t max_rows, void *d_out, void *hip_stream);
 
+/*
+ * The gather stage of smfg_sample_mfg_many on its own, for callers that run it on another stream
+ * than the sampling stages (a call with outs[b].features == NULL skips the gather; this function
+ * does it later): for every batch b, rows j < counts[L] of outs[b].features are copied from the
+ * feature rows outs[b].node_ids[j]; a batch whose status word is non-zero is skipped.  One launch
+ * for all batches.  The caller orders it after the sampling call (same stream, or an event).
+ */
+int smfg_gather_many(const smfg_graph_t *g, const smfg_output_t *outs, int32_t num_batches,
+                     int32_t L, void *hip_stream);
+
 /* Copies counts[0 .. 2L+2) to the host after synchronising the stream; returns SMFG_OK or, if the
  * status word is non-zero, its (positive) SMFG_ST_* value. */
 int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, void *hip_stream);

@@ -28,7 +28,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsmfg.so"
 EXPORTS = [
     "smfg_graph_create", "smfg_graph_destroy", "smfg_bounds", "smfg_workspace_create",
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
-    "smfg_gather_rows", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
+    "smfg_gather_rows", "smfg_gather_many", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
 STAGES = ["clear", "seeds", "sample_insert", "flag_rows", "scan_tiles", "unused", "assemble", "gather"]
 
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
         L.smfg_sample_mfg_many.argtypes = [vp, pp, pp, ctypes.POINTER(i32), ctypes.POINTER(i32), i32,
                                            ctypes.POINTER(u64), ctypes.POINTER(_Output), i32, vp]
         L.smfg_gather_rows.argtypes = [vp, vp, vp, i64, vp, vp]
+        L.smfg_gather_many.argtypes = [vp, ctypes.POINTER(_Output), i32, i32, vp]
         L.smfg_read_counts.argtypes = [ctypes.POINTER(_Output), i32, ctypes.POINTER(i64), vp]
         L.smfg_profile_begin.argtypes = [i32, i32]
         L.smfg_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -220,9 +221,23 @@ def sample_mfg(g: Graph, ws: Workspace, seeds: torch.Tensor, fanouts: Sequence[i
     _check(rc, "smfg_sample_mfg")
 
 
+def _out_array(outs: Sequence[Output], with_features: bool = True):
+    a = (_Output * len(outs))()
+    for i, o in enumerate(outs):
+        ctypes.memmove(ctypes.byref(a[i]), ctypes.byref(o.c), ctypes.sizeof(_Output))
+        if not with_features:
+            a[i].features = None
+    return a
+
+
+def gather_many(g: Graph, outs: Sequence[Output], stream: Optional[torch.cuda.Stream] = None) -> None:
+    rc = lib().smfg_gather_many(g.handle, _out_array(outs), len(outs), outs[0].L, _stream_ptr(stream))
+    _check(rc, "smfg_gather_many")
+
+
 def sample_mfg_many(g: Graph, wss: Sequence[Workspace], seeds: Sequence[torch.Tensor], fanouts: Sequence[int],
                     rng_keys: Sequence[int], outs: Sequence[Output],
-                    stream: Optional[torch.cuda.Stream] = None) -> None:
+                    stream: Optional[torch.cuda.Stream] = None, with_features: bool = True) -> None:
     n = len(wss)
     assert len(seeds) == n and len(rng_keys) == n and len(outs) == n
     for s in seeds:
@@ -231,9 +246,7 @@ def sample_mfg_many(g: Graph, wss: Sequence[Workspace], seeds: Sequence[torch.Te
     a_seeds = (ctypes.c_void_p * n)(*[_ptr(s) for s in seeds])
     a_ns = (ctypes.c_int32 * n)(*[s.numel() for s in seeds])
     a_keys = (ctypes.c_uint64 * n)(*[k & 0xFFFFFFFFFFFFFFFF for k in rng_keys])
-    a_outs = (_Output * n)()
-    for i, o in enumerate(outs):
-        ctypes.memmove(ctypes.byref(a_outs[i]), ctypes.byref(o.c), ctypes.sizeof(_Output))
+    a_outs = _out_array(outs, with_features)
     rc = lib().smfg_sample_mfg_many(g.handle, a_ws, a_seeds, a_ns, _fan(fanouts), len(fanouts), a_keys,
                                     a_outs, n, _stream_ptr(stream))
     _check(rc, "smfg_sample_mfg_many")

@@ -509,8 +509,10 @@ template <typename V>
 __global__ void __launch_bounds__(kThreads) k_gather(const Launch P) {
   const BatchCtx& B = P.b[blockIdx.y];
   if (status_of(B, P.L) != 0) return;
-  gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), B.node_ids,
-                 B.counts[P.L], B.features);
+  int64_t n = B.counts[P.L];
+  if (n > B.node_capacity) n = B.node_capacity;
+  gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), B.node_ids, n,
+                 B.features);
 }
 
 template <typename V>
@@ -632,6 +634,19 @@ int check_fanouts(int32_t L, const int32_t* fanouts) {
   for (int h = 0; h < L; ++h)
     if (fanouts[h] < 1 || fanouts[h] > SMFG_MAX_FANOUT) return SMFG_ERR_BAD_FANOUT;
   return SMFG_OK;
+}
+
+// The gather launch shared by smfg_sample_mfg_many and smfg_gather_many.
+void launch_gather(const Launch& P, int64_t max_rows, int vb, unsigned G, hipStream_t st) {
+  const unsigned gb = blocks_for(max_rows, kGatherRows, 0x7FFFFFFFu);
+  StageTimer t_(SMFG_STAGE_GATHER, st);
+  switch (vb) {
+    case 16: k_gather<u32x4><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    case 8: k_gather<u32x2><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    case 4: k_gather<uint32_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    case 2: k_gather<uint16_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    default: k_gather<uint8_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+  }
 }
 
 }  // namespace
@@ -899,17 +914,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       k_assemble<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
     }
   }
-  if (want_feat) {
-    const unsigned gb = blocks_for(max_n[L], kGatherRows, 0x7FFFFFFFu);
-    StageTimer t_(SMFG_STAGE_GATHER, st);
-    switch (vb) {
-      case 16: k_gather<u32x4><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-      case 8: k_gather<u32x2><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-      case 4: k_gather<uint32_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-      case 2: k_gather<uint16_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-      default: k_gather<uint8_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-    }
-  }
+  if (want_feat) launch_gather(P, max_n[L], vb, G, st);
   hipError_t e = hipGetLastError();
   if (cur != g->device) (void)hipSetDevice(cur);
   return hip_err(e);
@@ -920,6 +925,44 @@ int smfg_sample_mfg(const smfg_graph_t* g, smfg_workspace_t* ws, const int32_t* 
                     void* hip_stream) {
   if (!out) return SMFG_ERR_NULL_PTR;
   return smfg_sample_mfg_many(g, &ws, &d_seeds, &num_seeds, fanouts, L, &rng_key, out, 1, hip_stream);
+}
+
+int smfg_gather_many(const smfg_graph_t* g, const smfg_output_t* outs, int32_t num_batches, int32_t L,
+                     void* hip_stream) {
+  if (!g || !outs) return SMFG_ERR_NULL_PTR;
+  if (!g->feat) return SMFG_ERR_INVALID_ARG;
+  if (L < 1 || L > SMFG_MAX_LAYERS) return SMFG_ERR_TOO_MANY_LAYERS;
+  if (num_batches < 1 || num_batches > SMFG_MAX_BATCHES) return SMFG_ERR_INVALID_ARG;
+  Launch P;
+  std::memset(&P, 0, sizeof(P));
+  P.feat = g->feat;
+  P.row_bytes = g->row_bytes;
+  P.row_stride = g->row_stride;
+  P.num_nodes = g->num_nodes;
+  P.L = L;
+  P.G = num_batches;
+  int vb = 16;
+  int64_t max_rows = 1;
+  for (int b = 0; b < num_batches; ++b) {
+    const smfg_output_t& o = outs[b];
+    if (!o.node_ids || !o.counts || !o.features) return SMFG_ERR_NULL_PTR;
+    if (o.node_capacity < 1 || o.node_capacity > (1ll << 29)) return SMFG_ERR_INVALID_ARG;
+    const int v = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(o.features),
+                            g->row_bytes, g->row_stride);
+    if (v < vb) vb = v;
+    if (o.node_capacity > max_rows) max_rows = o.node_capacity;
+    P.b[b].counts = o.counts;
+    P.b[b].node_ids = o.node_ids;
+    P.b[b].features = static_cast<uint8_t*>(o.features);
+    P.b[b].node_capacity = static_cast<int32_t>(o.node_capacity);
+  }
+  int cur = 0;
+  (void)hipGetDevice(&cur);
+  if (cur != g->device) (void)hipSetDevice(g->device);
+  launch_gather(P, max_rows, vb, static_cast<unsigned>(num_batches), static_cast<hipStream_t>(hip_stream));
+  hipError_t e = hipGetLastError();
+  if (cur != g->device) (void)hipSetDevice(cur);
+  return hip_err(e);
 }
 
 int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int64_t* d_num_rows,
