@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--pipeline", type=int, default=1,
                     help="1: gather of launch set i runs on a second stream while set i+1 is sampled (two "
                          "buffer sets); 0: every launch set runs start to end on one stream (see --streams)")
+    ap.add_argument("--feat-dim", type=int, default=0, help="experiment: override the feature width")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
     ap.add_argument("--no-cpu", action="store_true")
@@ -118,6 +119,9 @@ def main():
     from paper_2110_08450_amd import binding as smfg, synth
 
     w = synth.WORKLOADS[args.workload]
+    if args.feat_dim:
+        import dataclasses
+        w = dataclasses.replace(w, feat_dim=args.feat_dim)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     t0 = time.time()
