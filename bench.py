@@ -138,12 +138,16 @@ def main():
     G = max(1, min(args.batches_per_call, smfg.MAX_BATCHES))
     L = len(w.fanouts)
     g = smfg.graph_create(graph.indptr, graph.indices, feat)
-    S = 2 if args.pipeline else max(1, args.streams)
-    streams = [torch.cuda.Stream() for _ in range(S)]
-    gather_done = [torch.cuda.Event() for _ in range(2)]
-    sampled = [torch.cuda.Event() for _ in range(2)]
-    wss = [[smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
-    outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
+    pipe = None
+    if args.pipeline:
+        from paper_2110_08450_amd.pipeline import BatchPipeline
+        pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G)
+        S, streams, wss, outs = 2, [pipe.s_sample, pipe.s_gather], pipe.wss, pipe.outs
+    else:
+        S = max(1, args.streams)
+        streams = [torch.cuda.Stream() for _ in range(S)]
+        wss = [[smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
+        outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
     row_bytes = g.row_bytes
 
     K = max(G, (args.steps // G) * G)
@@ -155,20 +159,15 @@ def main():
     last_call = {}   # buffer set -> first batch index of the last launch set that used it
 
     def run_pipelined(first, n):
-        s_sample, s_gather = streams
         for c in range(first, first + n, G):
             q = (c // G) % 2
             last_call[q] = c
             idx = [(c + b) % len(batches) for b in range(G)]
-            for b in range(G):
-                outs[q][b].c.counts = counts_all.data_ptr() + (c + b) * stride
-            s_sample.wait_event(gather_done[q])          # buffer set q is free again
-            smfg.sample_mfg_many(g, wss[q], [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx],
-                                 outs[q], stream=s_sample, with_features=False)
-            sampled[q].record(s_sample)
-            s_gather.wait_event(sampled[q])
-            smfg.gather_many(g, outs[q], stream=s_gather)
-            gather_done[q].record(s_gather)
+
+            def point_counts(os_, c=c):
+                for b, o in enumerate(os_):
+                    o.c.counts = counts_all.data_ptr() + (c + b) * stride
+            pipe.issue(q, [batches[i] for i in idx], [keys[i] for i in idx], before_launch=point_counts)
 
     def run_calls(first, n):
         if args.pipeline:

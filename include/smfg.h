@@ -85,6 +85,14 @@ int smfg_graph_create(smfg_graph_t **out, int64_t num_nodes, int64_t num_edges,
 int smfg_graph_destroy(smfg_graph_t *g);
 
 /*
+ * Optional label vector y (Listing 1: ys = y[ids[:batch_size]], the labels of the seed nodes).
+ * d_labels: device, num_nodes elements of elem_bytes (1, 2, 4 or 8) each, borrowed like the other
+ * arrays; NULL removes it.  A batch whose output has a non-NULL `labels` buffer then receives
+ * labels[i] = y[seed i], copied as opaque bytes.
+ */
+int smfg_graph_set_labels(smfg_graph_t *g, const void *d_labels, int32_t elem_bytes);
+
+/*
  * Worst-case sizes (host only, pure).  With disjoint neighbourhoods (section 3 draft text on
  * neighbourhood expansion) n_{h+1} <= min(num_nodes, n_h (1 + d_h)) and E_h <= n_h d_h.
  *   max_nodes host [L + 1], max_edges host [L].
@@ -113,6 +121,7 @@ typedef struct {
   int64_t *counts;                   /* [2L+2]: n_0..n_L, E_0..E_{L-1}, status                    */
   int64_t node_capacity;
   int64_t edge_capacity[SMFG_MAX_LAYERS];
+  void *labels;                      /* [num_seeds x label elem_bytes], or NULL (needs graph labels) */
 } smfg_output_t;
 
 /*

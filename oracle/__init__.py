@@ -38,6 +38,9 @@ def _configure(lib):
         lib.oracle_sample_positions.argtypes = [ctypes.c_uint32, ctypes.c_int32, ctypes.c_uint64,
                                                 ctypes.c_uint32, ctypes.c_uint32, u32p]
         lib.oracle_sample_positions.restype = ctypes.c_int32
+        lib.oracle_slice_labels.restype = ctypes.c_int32
+        lib.oracle_slice_labels.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p,
+                                            ctypes.c_int32, ctypes.c_void_p]
         lib.oracle_sample_mfg.restype = ctypes.c_int32
         lib.oracle_sample_mfg.argtypes = [
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
@@ -81,6 +84,18 @@ def sample_positions(deg: int, fanout: int, rng_key: int, v: int, h: int) -> Lis
     if n < 0:
         raise ValueError("bad fanout")
     return list(p[:n])
+
+
+def slice_labels(labels: np.ndarray, seeds: np.ndarray) -> np.ndarray:
+    """ys = y[ids[:batch_size]] for a 1-D label array of any fixed-size dtype."""
+    labels = np.ascontiguousarray(labels)
+    seeds = np.ascontiguousarray(seeds, dtype=np.int32)
+    out = np.empty(len(seeds), dtype=labels.dtype)
+    rc = _load().oracle_slice_labels(labels.ctypes.data, labels.itemsize, len(labels), seeds.ctypes.data,
+                                     len(seeds), out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_slice_labels: {rc}")
+    return out
 
 
 @dataclass

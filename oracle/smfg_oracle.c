@@ -99,6 +99,21 @@ int32_t oracle_sample_positions(uint32_t deg, int32_t d, uint64_t rng_key, uint3
   return k;
 }
 
+/* ---- label slice ---------------------------------------------------------------------------- */
+
+/* ys = y[ids[:batch_size]] (Listing 1): the first batch_size ids are the seeds themselves, so
+ * out[i] = y[seeds[i]], elem_bytes bytes each, copied verbatim. */
+int32_t oracle_slice_labels(const void *labels, int32_t elem_bytes, int64_t num_nodes,
+                            const int32_t *seeds, int32_t num_seeds, void *out) {
+  if (!labels || !seeds || !out || elem_bytes < 1) return ORACLE_ERR_ARG;
+  for (int32_t i = 0; i < num_seeds; ++i) {
+    if (seeds[i] < 0 || (int64_t)seeds[i] >= num_nodes) return ORACLE_ST_SEED_RANGE;
+    memcpy((char *)out + (int64_t)i * elem_bytes, (const char *)labels + (int64_t)seeds[i] * elem_bytes,
+           (size_t)elem_bytes);
+  }
+  return ORACLE_OK;
+}
+
 /* ---- multi-hop MFG + feature slice ------------------------------------------------------- */
 
 /*

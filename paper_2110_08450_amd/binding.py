@@ -26,7 +26,7 @@ ST_NODE_CAPACITY, ST_EDGE_CAPACITY, ST_TABLE_FULL, ST_SEED_OUT_OF_RANGE, ST_DUPL
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsmfg.so")
 
 EXPORTS = [
-    "smfg_graph_create", "smfg_graph_destroy", "smfg_bounds", "smfg_workspace_create",
+    "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_set_labels", "smfg_bounds", "smfg_workspace_create",
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
     "smfg_gather_rows", "smfg_gather_many", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
@@ -48,6 +48,7 @@ class _Output(ctypes.Structure):
         ("counts", ctypes.c_void_p),
         ("node_capacity", ctypes.c_int64),
         ("edge_capacity", ctypes.c_int64 * MAX_LAYERS),
+        ("labels", ctypes.c_void_p),
     ]
 
 
@@ -64,6 +65,7 @@ def lib() -> ctypes.CDLL:
         pp = ctypes.POINTER(ctypes.c_void_p)
         L.smfg_graph_create.argtypes = [pp, i64, i64, vp, vp, vp, i32, i32, i64]
         L.smfg_graph_destroy.argtypes = [vp]
+        L.smfg_graph_set_labels.argtypes = [vp, vp, i32]
         L.smfg_bounds.argtypes = [i32, i32, ctypes.POINTER(i32), i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.smfg_workspace_create.argtypes = [pp, vp, i32, i32, ctypes.POINTER(i32), i64]
         L.smfg_workspace_destroy.argtypes = [vp]
@@ -114,6 +116,7 @@ class Graph:
 
     def __init__(self, handle, indptr, indices, feat):
         self.handle, self.indptr, self.indices, self.feat = handle, indptr, indices, feat
+        self.labels = None
         self.num_nodes = int(indptr.numel() - 1)
         self.row_bytes = int(feat.shape[1] * feat.element_size()) if feat is not None else 0
 
@@ -138,6 +141,17 @@ def graph_create(indptr: torch.Tensor, indices: torch.Tensor, feat: Optional[tor
                                  fd, eb, stride)
     _check(rc, "smfg_graph_create")
     return Graph(h, indptr, indices, feat)
+
+
+def graph_set_labels(g: Graph, labels: Optional[torch.Tensor]) -> None:
+    """y: one element per node (1, 2, 4 or 8 bytes each), on the graph's device."""
+    if labels is None:
+        _check(lib().smfg_graph_set_labels(g.handle, None, 0), "smfg_graph_set_labels")
+    else:
+        assert labels.dim() == 1 and labels.is_contiguous() and labels.numel() == g.num_nodes
+        _check(lib().smfg_graph_set_labels(g.handle, ctypes.c_void_p(labels.data_ptr()), labels.element_size()),
+               "smfg_graph_set_labels")
+    g.labels = labels
 
 
 def bounds(num_seeds: int, fanouts: Sequence[int], num_nodes: int):
@@ -181,6 +195,7 @@ class Output:
     node_ids: torch.Tensor
     features: Optional[torch.Tensor]
     counts: torch.Tensor
+    labels: Optional[torch.Tensor] = None
     c: _Output = field(repr=False, default=None)
 
 
@@ -209,7 +224,11 @@ def alloc_output(g: Graph, max_seeds: int, fanouts: Sequence[int], node_capacity
     c.features = feats.data_ptr() if feats is not None else None
     c.counts = counts.data_ptr()
     c.node_capacity = ncap
-    return Output(L, ncap, ecap, indptr, indices, node_ids, feats, counts, c)
+    labels = None
+    if g.labels is not None:
+        labels = torch.empty(max(1, max_seeds), dtype=g.labels.dtype, device=dev)
+        c.labels = labels.data_ptr()
+    return Output(L, ncap, ecap, indptr, indices, node_ids, feats, counts, labels, c)
 
 
 def sample_mfg(g: Graph, ws: Workspace, seeds: torch.Tensor, fanouts: Sequence[int], rng_key: int,

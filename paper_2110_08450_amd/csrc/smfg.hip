@@ -63,6 +63,7 @@ struct BatchCtx {
   int32_t* blk_indptr;   // hop h
   int32_t* blk_indices;  // hop h
   uint8_t* features;
+  uint8_t* labels;       // [num_seeds x label bytes] or null
   int64_t edge_capacity; // hop h
   int32_t node_capacity;
   int32_t num_seeds;
@@ -75,9 +76,11 @@ struct Launch {
   const int64_t* indptr;
   const int32_t* indices;
   const uint8_t* feat;
+  const uint8_t* labels;  // y, label_bytes per node, or null
   int64_t row_bytes;
   int64_t row_stride;
   int64_t num_nodes;
+  int32_t label_bytes;
   int32_t L;       // hops of this call (counts layout)
   int32_t h;       // current hop
   int32_t d;       // its fanout
@@ -180,6 +183,16 @@ __global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
     if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
     else if (prev != 0xFFFFFFFFu) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
     B.node_ids[i] = v;
+    if (B.labels) {  // ys = y[ids[:batch_size]] (Listing 1): the seeds are the first ids
+      const uint8_t* src = P.labels + static_cast<int64_t>(v) * P.label_bytes;
+      uint8_t* dst = B.labels + static_cast<int64_t>(i) * P.label_bytes;
+      switch (P.label_bytes) {
+        case 8: *reinterpret_cast<uint64_t*>(dst) = *reinterpret_cast<const uint64_t*>(src); break;
+        case 4: *reinterpret_cast<uint32_t*>(dst) = *reinterpret_cast<const uint32_t*>(src); break;
+        case 2: *reinterpret_cast<uint16_t*>(dst) = *reinterpret_cast<const uint16_t*>(src); break;
+        default: *dst = *src; break;
+      }
+    }
   }
 }
 
@@ -589,6 +602,8 @@ struct smfg_graph {
   const int32_t* indices;
   const uint8_t* feat;
   int64_t row_bytes, row_stride;
+  const uint8_t* labels;
+  int32_t label_bytes;
   int device;
 };
 
@@ -678,6 +693,8 @@ int smfg_graph_create(smfg_graph_t** out, int64_t num_nodes, int64_t num_edges, 
   g->feat = static_cast<const uint8_t*>(d_feat);
   g->row_bytes = row_bytes;
   g->row_stride = d_feat ? row_stride_bytes : 0;
+  g->labels = nullptr;
+  g->label_bytes = 0;
   g->device = dev;
   *out = g;
   return SMFG_OK;
@@ -685,6 +702,20 @@ int smfg_graph_create(smfg_graph_t** out, int64_t num_nodes, int64_t num_edges, 
 
 int smfg_graph_destroy(smfg_graph_t* g) {
   delete g;
+  return SMFG_OK;
+}
+
+int smfg_graph_set_labels(smfg_graph_t* g, const void* d_labels, int32_t elem_bytes) {
+  if (!g) return SMFG_ERR_NULL_PTR;
+  if (!d_labels) {
+    g->labels = nullptr;
+    g->label_bytes = 0;
+    return SMFG_OK;
+  }
+  if (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8) return SMFG_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(d_labels) % static_cast<uintptr_t>(elem_bytes) != 0) return SMFG_ERR_INVALID_ARG;
+  g->labels = static_cast<const uint8_t*>(d_labels);
+  g->label_bytes = elem_bytes;
   return SMFG_OK;
 }
 
@@ -801,6 +832,8 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
   P.row_bytes = g->row_bytes;
   P.row_stride = g->row_stride;
   P.num_nodes = g->num_nodes;
+  P.labels = g->labels;
+  P.label_bytes = g->label_bytes;
   P.L = L;
   P.G = num_batches;
 
@@ -855,6 +888,12 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     B.rowoff = w->rowoff;
     B.tile_sums = w->tile_sums;
     B.features = static_cast<uint8_t*>(o.features);
+    if (o.labels) {
+      if (!g->labels) return SMFG_ERR_INVALID_ARG;
+      if (reinterpret_cast<uintptr_t>(o.labels) % static_cast<uintptr_t>(g->label_bytes) != 0)
+        return SMFG_ERR_INVALID_ARG;
+    }
+    B.labels = static_cast<uint8_t*>(o.labels);
     B.node_capacity = static_cast<int32_t>(o.node_capacity);
     B.num_seeds = num_seeds[b];
     B.key0 = static_cast<uint32_t>(rng_keys[b]);

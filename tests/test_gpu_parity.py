@@ -148,6 +148,27 @@ def test_ragged_batches_in_one_call(tiny):
         assert_same(fetch(outs[i], 3), gg.oracle.sample_mfg(seeds[i], fan, keys[i]), 3)
 
 
+@pytest.mark.parametrize("dtype", [np.int64, np.int32, np.int16, np.uint8])
+def test_label_slice(tiny, dtype):
+    """ys = y[ids[:batch_size]] (Listing 1) written by the same call."""
+    w, gg, batches = tiny
+    rng = np.random.default_rng(5)
+    y = rng.integers(0, 100, size=gg.g.num_nodes).astype(dtype)
+    g2 = smfg.graph_create(gg.indptr, gg.indices, gg.feat)
+    smfg.graph_set_labels(g2, torch.from_numpy(y).to(DEV))
+    ws = smfg.workspace_create(g2, 256, w.fanouts)
+    out = smfg.alloc_output(g2, 256, w.fanouts)
+    assert out.labels is not None and out.labels.dtype == torch.from_numpy(y).dtype
+    for b in (0, 3):
+        smfg.sample_mfg(g2, ws, batches[b].to(DEV), w.fanouts, 21, out)
+        res = fetch(out, 2)
+        assert_same(res, gg.oracle.sample_mfg(batches[b].numpy(), w.fanouts, 21), 2)
+        assert np.array_equal(out.labels[:256].cpu().numpy(), oracle.slice_labels(y, batches[b].numpy()))
+    # an output that asks for labels on a graph without labels is refused
+    with pytest.raises(smfg.SmfgError):
+        smfg.sample_mfg(gg.g, smfg.workspace_create(gg.g, 256, w.fanouts), batches[0].to(DEV), w.fanouts, 1, out)
+
+
 def test_empty_and_single_seed(tiny):
     w, gg, _ = tiny
     res = run_one(gg, np.zeros(0, dtype=np.int32), (3, 2), 5)
@@ -246,3 +267,33 @@ def test_mid_workload_sampled_batches():
         key = synth.batch_rng_key(w, b)
         smfg.sample_mfg(gg.g, ws, batches[b].to(DEV), w.fanouts, key, out)
         assert_same(fetch(out, L), gg.oracle.sample_mfg(batches[b].numpy(), w.fanouts, key), L)
+
+
+def test_pipelined_hand_off_matches_oracle():
+    """Two buffer sets, sampling and gather on side streams, the consumer on its own stream: every
+    yielded batch equals the oracle's, also when the consumer is slow or reads late."""
+    from paper_2110_08450_amd.pipeline import BatchPipeline
+    w = synth.WORKLOADS["mid"]
+    g = synth.make_graph(w)
+    f = synth.make_features(w)
+    gg = GpuGraph(g.indptr.numpy(), g.indices.numpy(), f.numpy())
+    batches = synth.make_seed_batches(w)[:11]
+    keys = [synth.batch_rng_key(w, b) for b in range(len(batches))]
+    L = len(w.fanouts)
+    pipe = BatchPipeline(gg.g, w.fanouts, w.batch_size, batches_per_set=3)
+    dev_batches = [b.to(DEV) for b in batches]
+    seen = 0
+    held = []
+    for outs in pipe.run(dev_batches, keys):
+        # consumer work on the current stream: copies that must see complete data
+        held = [(o.node_ids.clone(), o.features.clone(), o.counts.clone()) for o in outs]
+        burn = torch.randn(2048, 2048, device=DEV) @ torch.randn(2048, 2048, device=DEV)   # a slow consumer
+        for o, (ids, feats, cnt) in zip(outs, held):
+            ref = gg.oracle.sample_mfg(batches[seen].numpy(), w.fanouts, keys[seen])
+            assert_same(fetch(o, L), ref, L)
+            n = int(cnt[L].item())
+            assert np.array_equal(ids[:n].cpu().numpy(), ref.node_ids)
+            assert np.array_equal(feats[:n].cpu().numpy().view(np.uint8).reshape(n, -1), ref.features)
+            seen += 1
+        del burn
+    assert seen == len(batches)

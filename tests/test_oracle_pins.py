@@ -305,6 +305,17 @@ def test_chi_square_uniform_subsets(n, k):
 # error reporting
 # ---------------------------------------------------------------------------------------------
 
+@pytest.mark.parametrize("dtype", [np.int64, np.int32, np.int16, np.uint8, np.float32])
+def test_label_slice_is_plain_indexing(dtype):
+    """Listing 1: ys = y[ids[:batch_size]]; the first ids are the seeds."""
+    rng = np.random.default_rng(2)
+    y = rng.integers(0, 120, size=500).astype(dtype)
+    seeds = rng.choice(500, size=64, replace=False).astype(np.int32)
+    assert np.array_equal(oracle.slice_labels(y, seeds), y[seeds])
+    with pytest.raises(ValueError):
+        oracle.slice_labels(y, np.array([500], dtype=np.int32))
+
+
 def test_status_codes():
     adj = [[1, 2, 3], [0], [0], [0]]
     indptr, indices = csr_from_adj(adj)
