@@ -214,6 +214,32 @@ def main():
     alone_ms, alone_launches = smfg.profile_end()["gather"]
     alone_gbs = 2 * row_bytes * rows_alone / (alone_ms * 1e-3) / 1e9 if alone_ms > 0 else 0.0
 
+    # A consumer of the prepared batches (not part of the timed path): GraphSAGE mean aggregation
+    # over the outermost block of the batches of the last launch set.
+    consumer = None
+    if feat.dtype in (torch.float16, torch.float32):
+        q = timed_sets[0]
+        c0 = last_call[q] - W
+        agg_out = torch.empty((outs[q][0].node_capacity, w.feat_dim), dtype=torch.float32, device=dev)
+        smfg.profile_begin(2, 4 * G)
+        agg_bytes = 0
+        for rep in range(2):
+            for b in range(G):
+                o, c = outs[q][b], cnt[c0 + b]
+                o.c.counts = counts_all.data_ptr() + (W + c0 + b) * stride
+                n_dst, e_last = c[L - 1], c[2 * L]
+                cview = counts_all[W + c0 + b]
+                smfg.mean_aggregate(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.node_capacity, o.features,
+                                    agg_out, stream=streams[0])
+                agg_bytes += e_last * row_bytes + 4 * e_last + 4 * (n_dst + 1) + 4 * w.feat_dim * n_dst
+        torch.cuda.synchronize()
+        agg_ms, agg_n = smfg.profile_end()["mean_aggregate"]
+        consumer = {"kernel": "k_mean_aggregate", "block": f"hop {L - 1}", "launches": agg_n,
+                    "avg_launch_ms": agg_ms / max(1, agg_n),
+                    "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else 0.0, "unit": "GB/s",
+                    "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if agg_ms > 0 else 0.0}
+        del agg_out
+
     result = {
         "metric": "sampled mini-batches/sec (MFG build + feature gather)",
         "value": K / dt, "unit": "batches/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -238,6 +264,9 @@ def main():
                      "alone_avg_launch_ms": alone_ms / max(1, alone_launches),
                      "algorithmic_bytes_per_launch": gather_bytes / max(1, gather_launches)},
     }
+
+    if consumer is not None:
+        result["consumer"] = consumer
 
     if args.stages:
         smfg.profile_begin(2, 64 * (K // G))

@@ -164,6 +164,21 @@ int smfg_gather_rows(const smfg_graph_t *g, const int32_t *d_node_ids, const int
 int smfg_gather_many(const smfg_graph_t *g, const smfg_output_t *outs, int32_t num_batches,
                      int32_t L, void *hip_stream);
 
+/*
+ * A consumer of one MFG block: the mean aggregation of a GraphSAGE layer (Appendix C, GraphSAGE
+ * listing: x_target = x[:size[1]], conv((x, x_target), edge_index); equation 1 with agg = mean):
+ *   out[i, :] = (1 / k_i) * sum over e in [indptr[i], indptr[i+1]) of float(x[indices[e], :]),
+ * k_i = indptr[i+1] - indptr[i]; a destination without samples gets zeros.  i < *d_num_dst (a device
+ * int64, e.g. &counts[h]); max_dst bounds the launch.  x: device, row-major [num_src x dim], dense,
+ * elem_bytes 2 (IEEE half) or 4 (float); out: device float [max_dst x dim].  Sums run in float in
+ * slot order, then one division: the error of an output is at most k_i * 2^-24 times the mean of
+ * the magnitudes added (k_i - 1 rounded additions and one rounded division).  Asynchronous on
+ * hip_stream.
+ */
+int smfg_mean_aggregate(const int32_t *d_indptr, const int32_t *d_indices, const int64_t *d_num_dst,
+                        int64_t max_dst, const void *d_x, int32_t dim, int32_t elem_bytes,
+                        float *d_out, void *hip_stream);
+
 /* Copies counts[0 .. 2L+2) to the host after synchronising the stream; returns SMFG_OK or, if the
  * status word is non-zero, its (positive) SMFG_ST_* value. */
 int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, void *hip_stream);
@@ -183,7 +198,8 @@ int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, voi
 #define SMFG_STAGE_SCAN_ROWS 5
 #define SMFG_STAGE_ASSEMBLE 6
 #define SMFG_STAGE_GATHER 7
-#define SMFG_NUM_STAGES 8
+#define SMFG_STAGE_AGGREGATE 8
+#define SMFG_NUM_STAGES 9
 int smfg_profile_begin(int32_t level, int32_t max_records);
 int smfg_profile_end(double *stage_ms /* host [SMFG_NUM_STAGES] */,
                      int64_t *stage_launches /* host [SMFG_NUM_STAGES] */);

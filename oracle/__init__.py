@@ -41,6 +41,11 @@ def _configure(lib):
         lib.oracle_slice_labels.restype = ctypes.c_int32
         lib.oracle_slice_labels.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p,
                                             ctypes.c_int32, ctypes.c_void_p]
+        lib.oracle_half_to_double.restype = ctypes.c_double
+        lib.oracle_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.oracle_mean_aggregate.restype = ctypes.c_int32
+        lib.oracle_mean_aggregate.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                              ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_sample_mfg.restype = ctypes.c_int32
         lib.oracle_sample_mfg.argtypes = [
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
@@ -96,6 +101,25 @@ def slice_labels(labels: np.ndarray, seeds: np.ndarray) -> np.ndarray:
     if rc != 0:
         raise ValueError(f"oracle_slice_labels: {rc}")
     return out
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().oracle_half_to_double(bits & 0xFFFF))
+
+
+def mean_aggregate(indptr: np.ndarray, indices: np.ndarray, x: np.ndarray):
+    """(mean, mag) in float64 for one block; x is a 2-D float16 or float32 array of source rows."""
+    indptr = np.ascontiguousarray(indptr, dtype=np.int32)
+    indices = np.ascontiguousarray(indices, dtype=np.int32)
+    assert x.ndim == 2 and x.flags["C_CONTIGUOUS"] and x.dtype in (np.float16, np.float32)
+    n, dim = len(indptr) - 1, x.shape[1]
+    mean = np.zeros((n, dim), dtype=np.float64)
+    mag = np.zeros((n, dim), dtype=np.float64)
+    rc = _load().oracle_mean_aggregate(indptr.ctypes.data, indices.ctypes.data, n, x.ctypes.data, dim,
+                                       x.itemsize, mean.ctypes.data, mag.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_mean_aggregate: {rc}")
+    return mean, mag
 
 
 @dataclass

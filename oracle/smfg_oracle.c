@@ -5,7 +5,8 @@
  * node-wise neighbour sampling (paper section 2.2 and section 4.1, first paragraph), the
  * one-hop message-flow-graph construction with its ordered global->local map (the MFG
  * construction algorithm, procedure OneHopMFG), chained over hops (section 4.1), and the
- * slice xs = x[ids] of Listing 1.
+ * slice xs = x[ids] of Listing 1; plus the label slice of Listing 1 and, as a consumer of the
+ * blocks, the mean aggregation of equation 1 / the GraphSAGE listing of Appendix C.
  *
  * Only tests, the smoke check and the CPU-baseline leg of the benchmark may use this file.
  * It shares nothing with the HIP library: no header, no table, no helper.
@@ -110,6 +111,51 @@ int32_t oracle_slice_labels(const void *labels, int32_t elem_bytes, int64_t num_
     if (seeds[i] < 0 || (int64_t)seeds[i] >= num_nodes) return ORACLE_ST_SEED_RANGE;
     memcpy((char *)out + (int64_t)i * elem_bytes, (const char *)labels + (int64_t)seeds[i] * elem_bytes,
            (size_t)elem_bytes);
+  }
+  return ORACLE_OK;
+}
+
+/* ---- mean aggregation over one block (a consumer of the MFG) ------------------------------- */
+
+/* IEEE 754 binary16 bit pattern -> double (exact). */
+double oracle_half_to_double(uint16_t h) {
+  int sign = (h >> 15) & 1, ex = (h >> 10) & 0x1F, man = h & 0x3FF;
+  double v;
+  if (ex == 0) {
+    v = (double)man / 1024.0 / 16384.0;              /* subnormal: man * 2^-24 */
+  } else if (ex == 31) {
+    v = man ? (0.0 / 0.0) : (1.0 / 0.0);
+  } else {
+    v = 1.0 + (double)man / 1024.0;
+    int e = ex - 15;
+    while (e > 0) { v *= 2.0; --e; }
+    while (e < 0) { v *= 0.5; ++e; }
+  }
+  return sign ? -v : v;
+}
+
+/* Equation 1 with agg = mean, as the GraphSAGE listing of Appendix C uses a block:
+ * mean[i, c] = (1/k_i) sum_e x[indices[e], c] over the row i of the block, 0 for an empty row;
+ * also mag[i, c] = (1/k_i) sum_e |x[indices[e], c]| (the scale of the float error bound).
+ * x: row-major [num_src x dim] of elem_bytes 2 (half) or 4 (float).  All sums in double. */
+int32_t oracle_mean_aggregate(const int32_t *indptr, const int32_t *indices, int64_t num_dst,
+                              const void *x, int32_t dim, int32_t elem_bytes, double *mean, double *mag) {
+  if (!indptr || !indices || !x || !mean || !mag || dim < 1 || (elem_bytes != 2 && elem_bytes != 4))
+    return ORACLE_ERR_ARG;
+  for (int64_t i = 0; i < num_dst; ++i) {
+    int32_t k = indptr[i + 1] - indptr[i];
+    for (int32_t c = 0; c < dim; ++c) {
+      double s = 0.0, a = 0.0;
+      for (int32_t e = indptr[i]; e < indptr[i + 1]; ++e) {
+        int64_t at = (int64_t)indices[e] * dim + c;
+        double v = elem_bytes == 2 ? oracle_half_to_double(((const uint16_t *)x)[at])
+                                   : (double)((const float *)x)[at];
+        s += v;
+        a += v < 0 ? -v : v;
+      }
+      mean[i * dim + c] = k > 0 ? s / k : 0.0;
+      mag[i * dim + c] = k > 0 ? a / k : 0.0;
+    }
   }
   return ORACLE_OK;
 }

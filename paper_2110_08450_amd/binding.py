@@ -28,9 +28,10 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsmfg.so"
 EXPORTS = [
     "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_set_labels", "smfg_bounds", "smfg_workspace_create",
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
-    "smfg_gather_rows", "smfg_gather_many", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
+    "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
-STAGES = ["clear", "seeds", "sample_insert", "flag_rows", "scan_tiles", "unused", "assemble", "gather"]
+STAGES = ["clear", "seeds", "sample_insert", "flag_rows", "scan_tiles", "unused", "assemble", "gather",
+          "mean_aggregate"]
 
 
 class SmfgError(RuntimeError):
@@ -77,6 +78,7 @@ def lib() -> ctypes.CDLL:
                                            ctypes.POINTER(u64), ctypes.POINTER(_Output), i32, vp]
         L.smfg_gather_rows.argtypes = [vp, vp, vp, i64, vp, vp]
         L.smfg_gather_many.argtypes = [vp, ctypes.POINTER(_Output), i32, i32, vp]
+        L.smfg_mean_aggregate.argtypes = [vp, vp, vp, i64, vp, i32, i32, vp, vp]
         L.smfg_read_counts.argtypes = [ctypes.POINTER(_Output), i32, ctypes.POINTER(i64), vp]
         L.smfg_profile_begin.argtypes = [i32, i32]
         L.smfg_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -277,6 +279,20 @@ def gather_rows(g: Graph, node_ids: torch.Tensor, num_rows: torch.Tensor, max_ro
     rc = lib().smfg_gather_rows(g.handle, _ptr(node_ids), ctypes.c_void_p(num_rows.data_ptr()), max_rows,
                                 ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc, "smfg_gather_rows")
+
+
+def mean_aggregate(indptr: torch.Tensor, indices: torch.Tensor, num_dst: torch.Tensor, max_dst: int,
+                   x: torch.Tensor, out: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """out[i] = mean of x[indices[e]] over the block row i (float32 out; x is float16 or float32)."""
+    assert indptr.dtype == torch.int32 and indices.dtype == torch.int32 and num_dst.dtype == torch.int64
+    assert x.dim() == 2 and x.is_contiguous() and x.dtype in (torch.float16, torch.float32)
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape[1] == x.shape[1]
+    assert out.shape[0] >= max_dst
+    rc = lib().smfg_mean_aggregate(ctypes.c_void_p(indptr.data_ptr()), ctypes.c_void_p(indices.data_ptr()),
+                                   ctypes.c_void_p(num_dst.data_ptr()), max_dst, ctypes.c_void_p(x.data_ptr()),
+                                   x.shape[1], x.element_size(), ctypes.c_void_p(out.data_ptr()),
+                                   _stream_ptr(stream))
+    _check(rc, "smfg_mean_aggregate")
 
 
 def read_counts(out: Output, stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> List[int]:

@@ -539,6 +539,56 @@ __global__ void __launch_bounds__(kThreads) k_gather_plain(const uint8_t* feat, 
   gather_rows<V>(feat, row_stride, static_cast<uint32_t>(row_bytes / sizeof(V)), ids, n, out);
 }
 
+// ---- a consumer: GraphSAGE mean aggregation over one block -------------------------------------
+// 16 lanes per destination; a lane owns V consecutive columns per round of 16 * V columns and
+// accumulates its destination's sampled source rows in float, slot order, two rows in flight.
+constexpr int kAggLanes = 16;
+constexpr int kAggRows = kThreads / kAggLanes;
+
+template <typename T, int V>
+struct alignas(sizeof(T) * V) RowVec {
+  T v[V];
+};
+
+__device__ __forceinline__ float to_float(_Float16 h) { return static_cast<float>(h); }
+__device__ __forceinline__ float to_float(float f) { return f; }
+
+template <typename T, int V>
+__global__ void __launch_bounds__(kThreads) k_mean_aggregate(const int32_t* __restrict__ indptr,
+                                                             const int32_t* __restrict__ indices,
+                                                             const int64_t* __restrict__ num_dst, int64_t max_dst,
+                                                             const T* __restrict__ x, int dim,
+                                                             float* __restrict__ out) {
+  int64_t n = *num_dst;
+  if (n > max_dst) n = max_dst;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kAggRows + threadIdx.x / kAggLanes;
+  if (i >= n) return;
+  const int lane = threadIdx.x & (kAggLanes - 1);
+  const int e0 = indptr[i], e1 = indptr[i + 1];
+  const float k = static_cast<float>(e1 - e0);
+  typedef RowVec<T, V> Vec;
+  for (int c = lane * V; c < dim; c += kAggLanes * V) {
+    float acc[V];
+#pragma unroll
+    for (int t = 0; t < V; ++t) acc[t] = 0.f;
+    int e = e0;
+    for (; e + 1 < e1; e += 2) {
+      const Vec a = *reinterpret_cast<const Vec*>(x + static_cast<int64_t>(indices[e]) * dim + c);
+      const Vec b = *reinterpret_cast<const Vec*>(x + static_cast<int64_t>(indices[e + 1]) * dim + c);
+#pragma unroll
+      for (int t = 0; t < V; ++t) acc[t] = (acc[t] + to_float(a.v[t])) + to_float(b.v[t]);
+    }
+    if (e < e1) {
+      const Vec a = *reinterpret_cast<const Vec*>(x + static_cast<int64_t>(indices[e]) * dim + c);
+#pragma unroll
+      for (int t = 0; t < V; ++t) acc[t] += to_float(a.v[t]);
+    }
+    float* o = out + i * dim + c;
+#pragma unroll
+    for (int t = 0; t < V; ++t) o[t] = e1 > e0 ? acc[t] / k : 0.f;
+  }
+}
+
 // ---- host side --------------------------------------------------------------------------------
 
 inline int hip_err(hipError_t e) { return e == hipSuccess ? SMFG_OK : SMFG_ERR_HIP_BASE - static_cast<int>(e); }
@@ -1028,6 +1078,37 @@ int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int
   hipError_t e = hipGetLastError();
   if (cur != g->device) (void)hipSetDevice(cur);
   return hip_err(e);
+}
+
+int smfg_mean_aggregate(const int32_t* d_indptr, const int32_t* d_indices, const int64_t* d_num_dst,
+                        int64_t max_dst, const void* d_x, int32_t dim, int32_t elem_bytes, float* d_out,
+                        void* hip_stream) {
+  if (!d_indptr || !d_indices || !d_num_dst || !d_x || !d_out) return SMFG_ERR_NULL_PTR;
+  if (dim < 1 || (elem_bytes != 2 && elem_bytes != 4) || max_dst < 0 || max_dst >= (1ll << 31))
+    return SMFG_ERR_INVALID_ARG;
+  if (max_dst == 0) return SMFG_OK;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const unsigned gb = blocks_for(max_dst, kAggRows, 0x7FFFFFFFu);
+  const uintptr_t ax = reinterpret_cast<uintptr_t>(d_x);
+  {
+    StageTimer t_(SMFG_STAGE_AGGREGATE, st);
+    if (elem_bytes == 2) {
+      const _Float16* x = static_cast<const _Float16*>(d_x);
+      if (dim % 8 == 0 && ax % 16 == 0)
+        k_mean_aggregate<_Float16, 8><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+      else if (dim % 2 == 0 && ax % 4 == 0)
+        k_mean_aggregate<_Float16, 2><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+      else
+        k_mean_aggregate<_Float16, 1><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+    } else {
+      const float* x = static_cast<const float*>(d_x);
+      if (dim % 4 == 0 && ax % 16 == 0)
+        k_mean_aggregate<float, 4><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+      else
+        k_mean_aggregate<float, 1><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+    }
+  }
+  return hip_err(hipGetLastError());
 }
 
 int smfg_read_counts(const smfg_output_t* out, int32_t L, int64_t* h_counts, void* hip_stream) {

@@ -297,3 +297,44 @@ def test_pipelined_hand_off_matches_oracle():
             seen += 1
         del burn
     assert seen == len(batches)
+
+
+@pytest.mark.parametrize("dim,dtype", [(128, np.float16), (100, np.float16), (33, np.float16),
+                                       (128, np.float32), (5, np.float32)])
+def test_mean_aggregate_consumer(dim, dtype):
+    """GraphSAGE mean aggregation over the blocks of a sampled batch, outermost hop first, feeding
+    each layer's output (cast back to the input type) to the next block, as the model listing of
+    Appendix C consumes an MFG.  Float sums in slot order, k - 1 rounded additions and one rounded
+    division: error <= k * 2^-24 * mean magnitude of the terms."""
+    rng = np.random.default_rng(dim)
+    adj = random_simple_graph(4000, 14, rng, hub=700)
+    adj[3] = []
+    adj = [[u for u in row if u != 3] for row in adj]
+    indptr, indices = csr_from_adj(adj)
+    feat = (rng.standard_normal((4000, dim)) * 4).astype(dtype)
+    gg = GpuGraph(indptr, indices, feat)
+    seeds = np.concatenate([[3], rng.choice(np.arange(4, 4000), size=700, replace=False)]).astype(np.int32)
+    fan = (7, 5, 3)
+    seeds_d = torch.from_numpy(seeds).to(DEV)
+    ws = smfg.workspace_create(gg.g, len(seeds), fan)
+    out = smfg.alloc_output(gg.g, len(seeds), fan)
+    smfg.sample_mfg(gg.g, ws, seeds_d, fan, 31, out)
+    res = fetch(out, 3)
+    ref = gg.oracle.sample_mfg(seeds, fan, 31)
+    assert_same(res, ref, 3)
+    x_gpu = out.features                       # [cap x dim], first n_3 rows valid
+    x_ref = ref.features.view(dtype).reshape(-1, dim)
+    for h in (2, 1, 0):
+        n_dst = res["n"][h]
+        y = torch.full((out.node_capacity, dim), float("nan"), dtype=torch.float32, device=DEV)
+        smfg.mean_aggregate(out.indptr[h], out.indices[h], out.counts[h:h + 1], out.node_capacity, x_gpu, y)
+        torch.cuda.synchronize()
+        mean, mag = oracle.mean_aggregate(ref.indptr[h], ref.indices[h], np.ascontiguousarray(x_ref))
+        got = y[:n_dst].cpu().numpy().astype(np.float64)
+        assert np.isnan(y[n_dst:].cpu().numpy()).all()          # nothing written past n_dst
+        k = np.diff(ref.indptr[h])
+        assert (np.abs(got - mean) <= k[:, None] * 2.0 ** -24 * mag).all(), f"hop {h}"
+        assert (got[k == 0] == 0).all()
+        # next layer: both sides continue from the GPU's float output cast to the input type
+        x_gpu = y[:n_dst].to(x_gpu.dtype).contiguous()
+        x_ref = x_gpu.cpu().numpy()

@@ -7,6 +7,7 @@ import ctypes
 import os
 import subprocess
 
+import numpy as np
 import pytest
 
 import oracle
@@ -40,6 +41,13 @@ MUTATIONS = [
     ("positions ignored: first k neighbours", "indices[a + (int64_t)p[s]]", "indices[a + (int64_t)s]"),
     ("feature row taken by local id", "(int64_t)node_ids[j] * row_stride", "j * row_stride"),
     ("block indptr shifted by one", "bp[i + 1] = (int32_t)e;", "bp[i] = (int32_t)e;"),
+    ("mean divides by k + 1", "mean[i * dim + c] = k > 0 ? s / k : 0.0;", "mean[i * dim + c] = k > 0 ? s / (k + 1) : 0.0;"),
+    ("mean reads the destination's own row", "int64_t at = (int64_t)indices[e] * dim + c;",
+     "int64_t at = (int64_t)i * dim + c;"),
+    ("half exponent bias off by one", "int e = ex - 15;", "int e = ex - 14;"),
+    ("half subnormals scaled as normals", "v = (double)man / 1024.0 / 16384.0;", "v = (double)man / 1024.0 / 32768.0;"),
+    ("label taken by position instead of node", "(const char *)labels + (int64_t)seeds[i] * elem_bytes",
+     "(const char *)labels + (int64_t)i * elem_bytes"),
     ("only the new frontier is expanded in the next hop", "for (int64_t i = 0; i < n_dst",
      "for (int64_t i = (h == 0 ? 0 : counts[h - 1]); i < n_dst"),
 ]
@@ -59,6 +67,9 @@ def _pins():
         yield lambda L=L: pins.test_full_neighbourhood_equals_bfs(L)
     yield pins.test_consumer_contract_prefix_and_last_block
     yield pins.test_keying_properties
+    yield lambda: pins.test_label_slice_is_plain_indexing(np.int32)
+    yield pins.test_half_decoding_matches_numpy_for_every_bit_pattern
+    yield lambda: pins.test_mean_aggregate_equals_sparse_matrix_product(np.float16)
     yield lambda: pins.test_chi_square_uniform_subsets(8, 3)
     yield lambda: pins.test_chi_square_uniform_subsets(40, 15)
 

@@ -316,6 +316,47 @@ def test_label_slice_is_plain_indexing(dtype):
         oracle.slice_labels(y, np.array([500], dtype=np.int32))
 
 
+def test_half_decoding_matches_numpy_for_every_bit_pattern():
+    """IEEE binary16 -> double against numpy's conversion, all 65536 patterns."""
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+@pytest.mark.parametrize("dtype", [np.float16, np.float32])
+def test_mean_aggregate_equals_sparse_matrix_product(dtype):
+    """Equation 1 with agg = mean over a block = (D^-1 A) X with A the block's CSR incidence matrix
+    (scipy.sparse product in float64); empty rows give zeros.  The block comes from the oracle's
+    own sampler so the shapes are the real ones (destinations are a prefix of the sources)."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(9)
+    adj = random_simple_graph(300, 9, rng)
+    adj[5] = []
+    adj = [[u for u in row if u != 5] for row in adj]
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    seeds = np.concatenate([[5], rng.choice(np.arange(6, 300), size=40, replace=False)]).astype(np.int32)
+    r = orc.sample_mfg(seeds, (4, 3), 17)
+    x = (rng.standard_normal((r.num_nodes[2], 24)) * 3).astype(dtype)
+    for h in (1, 0):
+        n_dst, n_src = r.num_nodes[h], r.num_nodes[h + 1]
+        xs = np.ascontiguousarray(x[:n_src])
+        mean, mag = oracle.mean_aggregate(r.indptr[h], r.indices[h], xs)
+        k = np.diff(r.indptr[h]).astype(np.float64)
+        a = sp.csr_matrix((np.ones(len(r.indices[h])), r.indices[h], r.indptr[h]), shape=(n_dst, n_src))
+        inv = np.divide(1.0, k, out=np.zeros_like(k), where=k > 0)
+        want = sp.diags(inv) @ (a @ xs.astype(np.float64))
+        want_mag = sp.diags(inv) @ (a @ np.abs(xs.astype(np.float64)))
+        assert np.allclose(mean, want, rtol=1e-13, atol=1e-13)
+        assert np.allclose(mag, want_mag, rtol=1e-13, atol=1e-13)
+        assert (mean[k == 0] == 0).all() and (k == 0).any() or h != 0
+        x = mean.astype(dtype)           # next layer's input has n_dst rows: the prefix property
+
+
 def test_status_codes():
     adj = [[1, 2, 3], [0], [0], [0]]
     indptr, indices = csr_from_adj(adj)
