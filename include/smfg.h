@@ -195,11 +195,10 @@ int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, voi
 #define SMFG_STAGE_SAMPLE 2
 #define SMFG_STAGE_FLAG 3
 #define SMFG_STAGE_SCAN_TILES 4
-#define SMFG_STAGE_SCAN_ROWS 5
-#define SMFG_STAGE_ASSEMBLE 6
-#define SMFG_STAGE_GATHER 7
-#define SMFG_STAGE_AGGREGATE 8
-#define SMFG_NUM_STAGES 9
+#define SMFG_STAGE_ASSEMBLE 5
+#define SMFG_STAGE_GATHER 6
+#define SMFG_STAGE_AGGREGATE 7
+#define SMFG_NUM_STAGES 8
 int smfg_profile_begin(int32_t level, int32_t max_records);
 int smfg_profile_end(double *stage_ms /* host [SMFG_NUM_STAGES] */,
                      int64_t *stage_launches /* host [SMFG_NUM_STAGES] */);

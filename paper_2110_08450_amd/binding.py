@@ -30,7 +30,7 @@ EXPORTS = [
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
     "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
-STAGES = ["clear", "seeds", "sample_insert", "flag_rows", "scan_tiles", "unused", "assemble", "gather",
+STAGES = ["clear", "seeds", "sample_insert", "flag_rows", "scan_tiles", "assemble", "gather",
           "mean_aggregate"]
 
 

@@ -382,3 +382,24 @@ def test_synthetic_workload_tiny(tiny_inputs):
         check_mfg(indptr, indices, seeds.numpy(), w.fanouts, r.node_ids, r.indptr, r.indices,
                   r.num_nodes, r.num_edges)
         assert np.array_equal(r.features.view(np.float32), feat.numpy()[r.node_ids])
+
+
+def test_small_workloads_match_stored_counts():
+    """tests/golden/workload_counts.json (written by make_workload_counts.py from the oracle):
+    the generators and the oracle still produce the same batches."""
+    import json
+    from paper_2110_08450_amd import synth
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "workload_counts.json")
+    stored = json.load(open(path))
+    for name, rec in stored.items():
+        w = synth.WORKLOADS[name]
+        g = synth.make_graph(w)
+        batches = synth.make_seed_batches(w)
+        assert g.num_edges == rec["num_edges"] and len(batches) == rec["num_batches"]
+        orc = oracle.Oracle(g.indptr.numpy(), g.indices.numpy())
+        for row in rec["batches"]:
+            b = row["batch"]
+            r = orc.sample_mfg(batches[b].numpy(), w.fanouts, synth.batch_rng_key(w, b))
+            assert r.num_nodes == row["nodes"] and r.num_edges == row["edges"]
+            assert r.node_ids[:4].tolist() == row["node_ids_head"]
+            assert r.node_ids[-4:].tolist() == row["node_ids_tail"]
