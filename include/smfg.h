@@ -14,6 +14,9 @@
  *      chained, the node list of hop h being the destination list of hop h+1 (section 4.1);
  *   3. the feature slice xs = x[ids] for the final node list (Listing 1).
  *
+ * A fanout may also be SMFG_FANOUT_ALL: the full neighbourhood, as the paper's inference
+ * experiments use it next to sampled fanouts (section 5, Table 6).
+ *
  * Conventions fixed where the paper is silent:
  *   - fanouts[0] belongs to hop 0, whose destinations are the seeds;
  *   - a node with degree <= d_h contributes its whole CSR row in CSR order (no random draw);
@@ -43,14 +46,16 @@ extern "C" {
 #endif
 
 #define SMFG_MAX_LAYERS 8
-#define SMFG_MAX_FANOUT 32
+#define SMFG_MAX_FANOUT 32         /* fanouts up to here take the fast path (one lane per slot)   */
+#define SMFG_MAX_WIDE_FANOUT 1024  /* larger fanouts, up to here, take the wide path               */
+#define SMFG_FANOUT_ALL (-1)       /* every neighbour (full neighbourhood, no draw); wide path     */
 #define SMFG_MAX_BATCHES 16 /* batches per smfg_sample_mfg_many call */
 
 /* host-detected errors (return values) */
 #define SMFG_OK 0
 #define SMFG_ERR_INVALID_ARG (-1)
 #define SMFG_ERR_NULL_PTR (-2)
-#define SMFG_ERR_BAD_FANOUT (-3)      /* d < 1 or d > SMFG_MAX_FANOUT */
+#define SMFG_ERR_BAD_FANOUT (-3)      /* d is neither SMFG_FANOUT_ALL nor in [1, SMFG_MAX_WIDE_FANOUT] */
 #define SMFG_ERR_TOO_MANY_LAYERS (-4) /* L < 1 or L > SMFG_MAX_LAYERS */
 #define SMFG_ERR_TOO_MANY_SEEDS (-5)  /* more seeds than the workspace / output was sized for */
 #define SMFG_ERR_OOM (-6)             /* scratch allocation failed */
@@ -95,7 +100,9 @@ int smfg_graph_set_labels(smfg_graph_t *g, const void *d_labels, int32_t elem_by
 /*
  * Worst-case sizes (host only, pure).  With disjoint neighbourhoods (section 3 draft text on
  * neighbourhood expansion) n_{h+1} <= min(num_nodes, n_h (1 + d_h)) and E_h <= n_h d_h.
- *   max_nodes host [L + 1], max_edges host [L].
+ *   max_nodes host [L + 1], max_edges host [L].  From the first hop with SMFG_FANOUT_ALL on, the
+ * bounds are num_nodes nodes and -1 (unknown without the degrees) edges; E_h never exceeds the
+ * graph's num_edges, because destinations are distinct.
  */
 int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t *fanouts, int64_t num_nodes,
                 int64_t *max_nodes, int64_t *max_edges);
@@ -108,6 +115,15 @@ int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t *fanouts, int64_t nu
  */
 int smfg_workspace_create(smfg_workspace_t **out, const smfg_graph_t *g, int32_t max_seeds,
                           int32_t L, const int32_t *fanouts, int64_t node_capacity);
+/*
+ * The same with an explicit bound on the samples of a single hop (sample_capacity >= max_h E_h;
+ * 0 = derive it from the fanouts as smfg_workspace_create does).  Needed when a fanout is
+ * SMFG_FANOUT_ALL, or when the derived worst case (destinations x fanout) would exceed the 2^30
+ * positions a hop can address.  A hop that draws more samples ends with SMFG_ST_EDGE_CAPACITY.
+ */
+int smfg_workspace_create_sized(smfg_workspace_t **out, const smfg_graph_t *g, int32_t max_seeds,
+                                int32_t L, const int32_t *fanouts, int64_t node_capacity,
+                                int64_t sample_capacity);
 int smfg_workspace_destroy(smfg_workspace_t *ws);
 /* Bytes of device scratch the workspace holds (0 for NULL). */
 int64_t smfg_workspace_bytes(const smfg_workspace_t *ws);

@@ -84,7 +84,7 @@ def floyd_positions(deg: int, k: int, words: Sequence[int]) -> List[int]:
 
 
 def sample_positions(deg: int, fanout: int, rng_key: int, v: int, h: int) -> List[int]:
-    p = (ctypes.c_uint32 * max(1, min(deg, fanout) if fanout >= 0 else 1))()
+    p = (ctypes.c_uint32 * max(1, min(deg, fanout) if fanout >= 0 else deg))()
     n = _load().oracle_sample_positions(deg, fanout, rng_key, v, h, p)
     if n < 0:
         raise ValueError("bad fanout")
@@ -143,11 +143,18 @@ class OracleMFG:
 
 
 def worst_case(num_seeds: int, fanouts: Sequence[int], num_nodes: int):
-    """n_{h+1} <= min(N, n_h (1 + d_h)) and E_h <= n_h d_h (disjoint-neighbourhood worst case)."""
+    """n_{h+1} <= min(N, n_h (1 + d_h)) and E_h <= n_h d_h (disjoint-neighbourhood worst case).
+    From the first fanout -1 (all neighbours) on: N nodes, and -1 (unknown) edges for such a hop."""
     nodes, edges = [min(num_seeds, num_nodes)], []
+    everything = False
     for d in fanouts:
-        edges.append(nodes[-1] * d)
-        nodes.append(min(num_nodes, nodes[-1] * (1 + d)))
+        everything = everything or d == -1
+        if everything:
+            edges.append(-1 if d == -1 else num_nodes * d)
+            nodes.append(num_nodes)
+        else:
+            edges.append(nodes[-1] * d)
+            nodes.append(min(num_nodes, nodes[-1] * (1 + d)))
     return nodes, edges
 
 
@@ -181,7 +188,9 @@ class Oracle:
         L = len(fanouts)
         wc_nodes, wc_edges = worst_case(len(seeds), fanouts, self.num_nodes)
         ncap = int(node_capacity) if node_capacity is not None else max(1, wc_nodes[-1])
-        ecap = np.asarray(edge_capacity if edge_capacity is not None else wc_edges, dtype=np.int64)
+        if edge_capacity is None:   # a hop never has more edges than the graph: destinations are distinct
+            edge_capacity = [min(e, len(self.indices)) if e >= 0 else len(self.indices) for e in wc_edges]
+        ecap = np.asarray(edge_capacity, dtype=np.int64)
         fan = np.asarray(fanouts, dtype=np.int32)
         node_ids = np.empty(ncap, dtype=np.int32)
         indptr = [np.zeros(ncap + 1, dtype=np.int32) for _ in range(L)]

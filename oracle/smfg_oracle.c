@@ -84,11 +84,12 @@ int32_t oracle_floyd_positions(uint32_t deg, uint32_t k, const uint32_t *words, 
   return (int32_t)k;
 }
 
-/* Positions within the CSR row of v chosen at hop h with fanout d; returns their number. */
+/* Positions within the CSR row of v chosen at hop h with fanout d; returns their number.
+ * d = -1 stands for the full neighbourhood (section 5 compares sampled fanouts with "all"). */
 int32_t oracle_sample_positions(uint32_t deg, int32_t d, uint64_t rng_key, uint32_t v, uint32_t h,
                                 uint32_t *p) {
-  if (d < 0) return ORACLE_ERR_ARG;
-  if (deg <= (uint32_t)d) {
+  if (d < -1) return ORACLE_ERR_ARG;
+  if (d == -1 || deg <= (uint32_t)d) {
     for (uint32_t s = 0; s < deg; ++s) p[s] = s;
     return (int32_t)deg;
   }
@@ -196,8 +197,8 @@ int32_t oracle_sample_mfg(int64_t num_nodes, const int64_t *indptr, const int32_
   uint32_t *p = NULL;
   for (int32_t h = 0; h < L && status == ORACLE_OK; ++h) {
     int32_t d = fanouts[h];
-    if (d < 1) { status = ORACLE_ERR_ARG; break; }
-    p = (uint32_t *)realloc(p, sizeof(uint32_t) * (size_t)d);
+    if (d < 1 && d != -1) { status = ORACLE_ERR_ARG; break; }
+    size_t p_cap = 0;
     int64_t n_dst = n; /* snapshot: nodes met during this hop are not expanded in it */
     int64_t e = 0;
     int32_t *bp = blk_indptr[h], *bi = blk_indices[h];
@@ -206,6 +207,8 @@ int32_t oracle_sample_mfg(int64_t num_nodes, const int64_t *indptr, const int32_
       int32_t v = node_ids[i];
       int64_t a = indptr[v];
       uint32_t deg = (uint32_t)(indptr[v + 1] - a);
+      size_t need = (d == -1 || deg <= (uint32_t)d) ? deg : (size_t)d;
+      if (need > p_cap) { p_cap = need; p = (uint32_t *)realloc(p, sizeof(uint32_t) * p_cap); }
       int32_t k = oracle_sample_positions(deg, d, rng_key, (uint32_t)v, (uint32_t)h, p);
       for (int32_t s = 0; s < k; ++s) {
         int32_t g = indices[a + (int64_t)p[s]];

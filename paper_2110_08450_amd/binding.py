@@ -16,6 +16,8 @@ import torch
 
 MAX_LAYERS = 8
 MAX_FANOUT = 32
+MAX_WIDE_FANOUT = 1024
+FANOUT_ALL = -1
 MAX_BATCHES = 16
 
 OK = 0
@@ -27,6 +29,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsmfg.so"
 
 EXPORTS = [
     "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_set_labels", "smfg_bounds", "smfg_workspace_create",
+    "smfg_workspace_create_sized",
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
     "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
@@ -69,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.smfg_graph_set_labels.argtypes = [vp, vp, i32]
         L.smfg_bounds.argtypes = [i32, i32, ctypes.POINTER(i32), i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.smfg_workspace_create.argtypes = [pp, vp, i32, i32, ctypes.POINTER(i32), i64]
+        L.smfg_workspace_create_sized.argtypes = [pp, vp, i32, i32, ctypes.POINTER(i32), i64, i64]
         L.smfg_workspace_destroy.argtypes = [vp]
         L.smfg_workspace_bytes.argtypes = [vp]
         L.smfg_workspace_bytes.restype = i64
@@ -178,10 +182,16 @@ class Workspace:
             self.handle = None
 
 
-def workspace_create(g: Graph, max_seeds: int, fanouts: Sequence[int], node_capacity: int = 0) -> Workspace:
+def workspace_create(g: Graph, max_seeds: int, fanouts: Sequence[int], node_capacity: int = 0,
+                     sample_capacity: int = 0) -> Workspace:
+    """sample_capacity > 0 bounds the samples of one hop explicitly (needed with FANOUT_ALL)."""
     h = ctypes.c_void_p()
-    rc = lib().smfg_workspace_create(ctypes.byref(h), g.handle, max_seeds, len(fanouts), _fan(fanouts),
-                                     node_capacity)
+    if sample_capacity:
+        rc = lib().smfg_workspace_create_sized(ctypes.byref(h), g.handle, max_seeds, len(fanouts), _fan(fanouts),
+                                               node_capacity, sample_capacity)
+    else:
+        rc = lib().smfg_workspace_create(ctypes.byref(h), g.handle, max_seeds, len(fanouts), _fan(fanouts),
+                                         node_capacity)
     _check(rc, "smfg_workspace_create")
     return Workspace(h)
 
@@ -207,8 +217,9 @@ def alloc_output(g: Graph, max_seeds: int, fanouts: Sequence[int], node_capacity
     L = len(fanouts)
     mn, me = bounds(max_seeds, fanouts, g.num_nodes)
     ncap = max(1, int(node_capacity if node_capacity is not None else mn[L]))
+    m = int(g.indices.numel())   # a hop never has more edges than the graph: destinations are distinct
     ecap = [int(x) for x in (edge_capacity if edge_capacity is not None
-                             else [min(me[h], ncap * fanouts[h]) for h in range(L)])]
+                             else [min(m, me[h], ncap * fanouts[h]) if fanouts[h] > 0 else m for h in range(L)])]
     dev = g.indptr.device
     indptr = [torch.empty(ncap + 1, dtype=torch.int32, device=dev) for _ in range(L)]
     indices = [torch.empty(max(1, ecap[h]), dtype=torch.int32, device=dev) for h in range(L)]

@@ -60,6 +60,10 @@ struct BatchCtx {
   int32_t* newrank;      // new nodes of the tile before this destination's first new node
   int32_t* rowoff;       // samples of the tile before this destination
   uint64_t* tile_sums;   // per tile: (edges << 32 | new nodes), later their exclusive scan
+  int64_t* rowstart;     // wide path: first CSR position of the destination's row
+  int32_t* rowdeg;       // wide path: degree of the destination
+  uint32_t* rank;        // wide path: new nodes of the sample's tile before this sample
+  uint64_t* stile_sums;  // wide path: per sample tile, new nodes, later their exclusive scan
   int32_t* blk_indptr;   // hop h
   int32_t* blk_indices;  // hop h
   uint8_t* features;
@@ -539,6 +543,233 @@ __global__ void __launch_bounds__(kThreads) k_gather_plain(const uint8_t* feat, 
   gather_rows<V>(feat, row_stride, static_cast<uint32_t>(row_bytes / sizeof(V)), ids, n, out);
 }
 
+// ---- wide path: fanouts above 32, or every neighbour (SMFG_FANOUT_ALL) ------------------------
+// Samples sit at their exact block offsets (pos = block indptr[i] + s), so a count + scan pass
+// comes first and the later passes walk the samples flat, four consecutive samples per thread.
+constexpr int kWideTile = 4 * kThreads;  // samples per flat tile
+
+// Degree, sample count and row start per destination; in-tile scan of the sample counts.
+__global__ void __launch_bounds__(kThreads) k_count_rows(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int d = P.d;
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const int i = tile * kTileRows + threadIdx.x;
+    uint32_t k = 0;
+    if (i < n) {
+      const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
+      const int64_t a = P.indptr[v];
+      const uint32_t deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
+      k = (d < 0 || deg <= static_cast<uint32_t>(d)) ? deg : static_cast<uint32_t>(d);
+      B.rowstart[i] = a;
+      B.rowdeg[i] = deg;
+      B.rowk[i] = static_cast<int32_t>(k);
+    }
+    unsigned long long total;
+    const unsigned long long pre = block_exscan(k, lds, total);
+    if (i < n) B.rowoff[i] = static_cast<int32_t>(pre);
+    if (threadIdx.x == 0) B.tile_sums[tile] = total;
+    __syncthreads();
+  }
+}
+
+// Exclusive scan of the per-tile sample counts; E_h and its capacity checks.
+__global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  unsigned long long carry = 0;
+  for (int t0 = 0; t0 < tiles; t0 += kThreads) {
+    const int t = t0 + threadIdx.x;
+    const unsigned long long x = t < tiles ? B.tile_sums[t] : 0ull;
+    unsigned long long total;
+    const unsigned long long ex = block_exscan(x, lds, total);
+    if (t < tiles) B.tile_sums[t] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    const bool fits = carry <= static_cast<unsigned long long>(B.edge_capacity) &&
+                      carry <= static_cast<unsigned long long>(B.lostto_entries);
+    B.counts[P.L + 1 + P.h] = static_cast<int64_t>(carry);
+    if (fits) B.blk_indptr[n] = static_cast<int32_t>(carry);
+    else set_status(B, P.L, SMFG_ST_EDGE_CAPACITY);
+  }
+}
+
+// One wave per destination; lane l of round r owns slot s = 64 r + l.
+__global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P) {
+  __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  uint32_t* picks = picks_lds[wave];
+  const int waves_total = gridDim.x * (kThreads / 64);
+  for (int i = blockIdx.x * (kThreads / 64) + wave; i < n; i += waves_total) {
+    const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
+    const int64_t a = B.rowstart[i];
+    const uint32_t deg = static_cast<uint32_t>(B.rowdeg[i]);
+    const uint32_t k = static_cast<uint32_t>(B.rowk[i]);
+    const uint32_t base = static_cast<uint32_t>(B.tile_sums[i / kTileRows]) + static_cast<uint32_t>(B.rowoff[i]);
+    if (lane == 0) B.blk_indptr[i] = static_cast<int32_t>(base);
+    const bool floyd = deg > k;  // only then are positions drawn (k = fanout <= SMFG_MAX_WIDE_FANOUT)
+    for (uint32_t s0 = 0; s0 < k; s0 += 64) {
+      const uint32_t s = s0 + static_cast<uint32_t>(lane);
+      const bool active = s < k;
+      uint32_t p = s;  // whole row in CSR order when nothing is drawn
+      if (floyd) {
+        uint32_t t = 0, j = 0;
+        if (active) {
+          const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), s >> 2, B.key0, B.key1, s & 3u);
+          j = deg - k + s;
+          t = __umulhi(w, j + 1u);  // index in [0, j]
+        }
+        // Floyd's rule slot by slot; the array set is picks[0, s0) in LDS plus the lanes of this round
+        const uint32_t round = k - s0 < 64u ? k - s0 : 64u;
+        for (uint32_t q = 0; q < round; ++q) {
+          const uint32_t tq = __shfl(t, static_cast<int>(q), 64);
+          bool hit = static_cast<uint32_t>(lane) < q && p == tq;
+          for (uint32_t l = static_cast<uint32_t>(lane); l < s0; l += 64) hit = hit || picks[l] == tq;
+          const bool any = __ballot(hit) != 0ull;
+          if (static_cast<uint32_t>(lane) == q) p = any ? j : tq;
+        }
+        if (active) picks[s] = p;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // later rounds read all lanes' picks
+        __builtin_amdgcn_wave_barrier();
+      }
+      if (active) {
+        const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
+        const uint32_t pos = base + s;
+        uint32_t slot;
+        bool full;
+        const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
+        if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
+        uint32_t e = prev;  // see k_sample_insert for the three cases
+        if (prev > (kPend | pos)) {
+          e = kSlot | slot;
+          if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
+        }
+        B.ent[pos] = e;
+        B.gsrc[pos] = static_cast<int32_t>(g);
+      }
+    }
+  }
+}
+
+// Flat over the samples: first appearances, their in-tile ranks, per-tile totals.
+__global__ void __launch_bounds__(kThreads) k_flag_flat(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) {
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < B.lostto_entries;
+         q += static_cast<int64_t>(gridDim.x) * kThreads)
+      B.lostto[q] = 0u;
+    return;
+  }
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
+    uint32_t first[4];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      first[u] = 0;
+      const uint32_t pos = p0 + u;
+      if (pos < E) {
+        const uint32_t lost = B.lostto[pos];
+        if (lost != 0u) {
+          B.ent[pos] = lost;
+          B.lostto[pos] = 0u;
+        } else {
+          first[u] = (B.ent[pos] & kTagMask) == kSlot ? 1u : 0u;
+        }
+      }
+      mine += first[u];
+    }
+    unsigned long long total;
+    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (p0 + u < E) B.rank[p0 + u] = pre;
+      pre += first[u];
+    }
+    if (threadIdx.x == 0) B.stile_sums[tile] = total;
+    __syncthreads();
+  }
+}
+
+// Exclusive scan of the per-tile counts of new nodes; n_{h+1} and its capacity check.
+__global__ void __launch_bounds__(kThreads) k_scan_flat_tiles(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  unsigned long long carry = 0;
+  for (uint32_t t0 = 0; t0 < tiles; t0 += kThreads) {
+    const uint32_t t = t0 + threadIdx.x;
+    const unsigned long long x = t < tiles ? B.stile_sums[t] : 0ull;
+    unsigned long long total;
+    const unsigned long long ex = block_exscan(x, lds, total);
+    if (t < tiles) B.stile_sums[t] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    const int64_t nodes = static_cast<int64_t>(n) + static_cast<int64_t>(carry);
+    B.counts[P.h + 1] = nodes;
+    if (nodes > B.node_capacity) set_status(B, P.L, SMFG_ST_NODE_CAPACITY);
+  }
+}
+
+// Flat over the samples: final local ids -> block indices; first appearances publish themselves.
+__global__ void __launch_bounds__(kThreads) k_assemble_flat(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const bool last = P.h == P.L - 1;
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint32_t tpre = n + static_cast<uint32_t>(B.stile_sums[tile]);
+    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t pos = p0 + u;
+      if (pos >= E) continue;
+      const uint32_t e = B.ent[pos];
+      const uint32_t tag = e & kTagMask;
+      uint32_t local = e;
+      if (tag == kSlot) {
+        local = tpre + B.rank[pos];
+        const uint32_t g = static_cast<uint32_t>(B.gsrc[pos]);
+        B.node_ids[local] = static_cast<int32_t>(g);
+        if (!last) B.table[e & ~kTagMask] = (static_cast<uint64_t>(g) << 32) | local;
+      } else if (tag != 0u) {  // kPend: same node as the sample at position q < pos
+        uint32_t q = e & ~kTagMask;
+        for (;;) {
+          const uint32_t eq = B.ent[q];
+          if ((eq & kTagMask) == kSlot) {  // q is the node's first appearance
+            local = n + static_cast<uint32_t>(B.stile_sums[q / kWideTile]) + B.rank[q];
+            break;
+          }
+          const uint32_t nxt = eq & ~kTagMask;  // strictly smaller position
+          if (nxt >= q) break;                  // cannot happen; guards the loop
+          q = nxt;
+        }
+      }
+      B.blk_indices[pos] = static_cast<int32_t>(local);
+    }
+  }
+}
+
 // ---- a consumer: GraphSAGE mean aggregation over one block -------------------------------------
 // 16 lanes per destination; a lane owns V consecutive columns per round of 16 * V columns and
 // accumulates its destination's sampled source rows in float, slot order, two rows in flight.
@@ -675,15 +906,21 @@ struct smfg_workspace {
   int32_t* newrank;
   int32_t* rowoff;
   uint64_t* tile_sums;
+  int64_t* rowstart;
+  int32_t* rowdeg;
+  uint32_t* rank;
+  uint64_t* stile_sums;
 };
 
 namespace {
 
-// Largest padded (destination, slot) index space any hop can need, given a node capacity.
+// Largest (destination, slot) index space any hop can need, given a node capacity; -1 when a hop
+// takes every neighbour (no bound without the degrees).
 int64_t slot_entries_needed(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t num_nodes,
                             int64_t node_capacity) {
   int64_t n = num_seeds < num_nodes ? num_seeds : num_nodes, need = 0;
   for (int h = 0; h < L; ++h) {
+    if (fanouts[h] < 0) return -1;
     if (n > node_capacity) n = node_capacity;
     const int64_t e = n * fanouts[h];
     if (e > need) need = e;
@@ -693,11 +930,17 @@ int64_t slot_entries_needed(int32_t num_seeds, int32_t L, const int32_t* fanouts
   return need;
 }
 
-int check_fanouts(int32_t L, const int32_t* fanouts) {
+// Valid fanouts; `wide` tells whether the call needs the exact-offset path.
+int check_fanouts(int32_t L, const int32_t* fanouts, bool* wide = nullptr) {
   if (L < 1 || L > SMFG_MAX_LAYERS) return SMFG_ERR_TOO_MANY_LAYERS;
   if (!fanouts) return SMFG_ERR_NULL_PTR;
-  for (int h = 0; h < L; ++h)
-    if (fanouts[h] < 1 || fanouts[h] > SMFG_MAX_FANOUT) return SMFG_ERR_BAD_FANOUT;
+  bool w = false;
+  for (int h = 0; h < L; ++h) {
+    const int d = fanouts[h];
+    if (d != SMFG_FANOUT_ALL && (d < 1 || d > SMFG_MAX_WIDE_FANOUT)) return SMFG_ERR_BAD_FANOUT;
+    if (d == SMFG_FANOUT_ALL || d > SMFG_MAX_FANOUT) w = true;
+  }
+  if (wide) *wide = w;
   return SMFG_OK;
 }
 
@@ -777,10 +1020,17 @@ int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t nu
   if (num_seeds < 0 || num_nodes < 0) return SMFG_ERR_INVALID_ARG;
   int64_t n = num_seeds < num_nodes ? num_seeds : num_nodes;
   max_nodes[0] = n;
+  bool all = false;
   for (int h = 0; h < L; ++h) {
-    max_edges[h] = n * fanouts[h];
-    n = n + max_edges[h];
-    if (n > num_nodes) n = num_nodes;
+    all = all || fanouts[h] == SMFG_FANOUT_ALL;
+    if (all) {
+      max_edges[h] = fanouts[h] == SMFG_FANOUT_ALL ? -1 : num_nodes * fanouts[h];
+      n = num_nodes;
+    } else {
+      max_edges[h] = n * fanouts[h];
+      n = n + max_edges[h];
+      if (n > num_nodes) n = num_nodes;
+    }
     max_nodes[h + 1] = n;
   }
   return SMFG_OK;
@@ -788,18 +1038,25 @@ int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t nu
 
 int smfg_workspace_create(smfg_workspace_t** out, const smfg_graph_t* g, int32_t max_seeds, int32_t L,
                           const int32_t* fanouts, int64_t node_capacity) {
+  return smfg_workspace_create_sized(out, g, max_seeds, L, fanouts, node_capacity, 0);
+}
+
+int smfg_workspace_create_sized(smfg_workspace_t** out, const smfg_graph_t* g, int32_t max_seeds, int32_t L,
+                                const int32_t* fanouts, int64_t node_capacity, int64_t sample_capacity) {
   if (!out) return SMFG_ERR_NULL_PTR;
   *out = nullptr;
   if (!g) return SMFG_ERR_NULL_PTR;
   int rc = check_fanouts(L, fanouts);
   if (rc != SMFG_OK) return rc;
-  if (max_seeds < 0 || node_capacity < 0) return SMFG_ERR_INVALID_ARG;
+  if (max_seeds < 0 || node_capacity < 0 || sample_capacity < 0) return SMFG_ERR_INVALID_ARG;
   int64_t mn[SMFG_MAX_LAYERS + 1], me[SMFG_MAX_LAYERS];
   smfg_bounds(max_seeds, L, fanouts, g->num_nodes, mn, me);
   if (node_capacity == 0 || node_capacity > mn[L]) node_capacity = mn[L];
   if (node_capacity < 1) node_capacity = 1;
   if (node_capacity < mn[0]) return SMFG_ERR_TOO_MANY_SEEDS;
-  const int64_t slots = slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity);
+  int64_t slots = slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity);
+  if (sample_capacity > 0) slots = sample_capacity;
+  if (slots < 0) return SMFG_ERR_INVALID_ARG;  // SMFG_FANOUT_ALL needs an explicit sample capacity
   if (slots >= (1ll << 30) || node_capacity > (1ll << 29)) return SMFG_ERR_CAPACITY;
 
   uint32_t lg = 10;
@@ -823,7 +1080,9 @@ int smfg_workspace_create(smfg_workspace_t** out, const smfg_graph_t* g, int32_t
   const int64_t b_rowk = align((node_capacity + 4) * 4);
   const int64_t b_mask = align((node_capacity + 4) * 4);
   const int64_t b_tiles = align(tiles * 8);
-  ws->bytes = b_table + 3 * b_slot + 4 * b_rowk + b_tiles;
+  const int64_t b_start = align((node_capacity + 4) * 8);
+  const int64_t b_stiles = align((ws->slot_entries / kWideTile + 2) * 8);
+  ws->bytes = b_table + 4 * b_slot + 5 * b_rowk + b_tiles + b_start + b_stiles;
   int cur = 0;
   (void)hipGetDevice(&cur);
   if (cur != g->device) (void)hipSetDevice(g->device);
@@ -843,7 +1102,11 @@ int smfg_workspace_create(smfg_workspace_t** out, const smfg_graph_t* g, int32_t
   ws->rowmask = reinterpret_cast<uint32_t*>(p); p += b_mask;
   ws->newrank = reinterpret_cast<int32_t*>(p); p += b_rowk;
   ws->rowoff = reinterpret_cast<int32_t*>(p); p += b_rowk;
-  ws->tile_sums = reinterpret_cast<uint64_t*>(p);
+  ws->tile_sums = reinterpret_cast<uint64_t*>(p); p += b_tiles;
+  ws->rowstart = reinterpret_cast<int64_t*>(p); p += b_start;
+  ws->rowdeg = reinterpret_cast<int32_t*>(p); p += b_rowk;
+  ws->rank = reinterpret_cast<uint32_t*>(p); p += b_slot;
+  ws->stile_sums = reinterpret_cast<uint64_t*>(p);
   // displacement notes start out clear; flag_rows clears whatever a call writes
   e = hipMemset(ws->lostto, 0, static_cast<size_t>(b_slot));
   if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -870,7 +1133,8 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
                          const int32_t* num_seeds, const int32_t* fanouts, int32_t L, const uint64_t* rng_keys,
                          const smfg_output_t* outs, int32_t num_batches, void* hip_stream) {
   if (!g || !ws || !d_seeds || !num_seeds || !rng_keys || !outs) return SMFG_ERR_NULL_PTR;
-  int rc = check_fanouts(L, fanouts);
+  bool wide = false;
+  int rc = check_fanouts(L, fanouts, &wide);
   if (rc != SMFG_OK) return rc;
   if (num_batches < 1 || num_batches > SMFG_MAX_BATCHES) return SMFG_ERR_INVALID_ARG;
 
@@ -891,6 +1155,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
   for (int h = 0; h <= L; ++h) max_n[h] = 0;
   uint32_t max_table_log2 = 0;
   int32_t max_seeds = 0;
+  int64_t max_entries = 0;
   bool want_feat = false;
   int vb = 16;
 
@@ -911,8 +1176,10 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     if (o.node_capacity < 1) return SMFG_ERR_INVALID_ARG;
     if (num_seeds[b] > w->max_seeds || num_seeds[b] > o.node_capacity) return SMFG_ERR_TOO_MANY_SEEDS;
     if (o.node_capacity > w->node_capacity) return SMFG_ERR_CAPACITY;
-    if (slot_entries_needed(num_seeds[b], L, fanouts, g->num_nodes, o.node_capacity) > w->slot_entries)
+    // fast path: padded positions must fit; wide path: E_h is checked on the device
+    if (!wide && slot_entries_needed(num_seeds[b], L, fanouts, g->num_nodes, o.node_capacity) > w->slot_entries)
       return SMFG_ERR_CAPACITY;
+    if (w->slot_entries > max_entries) max_entries = w->slot_entries;
     if (g->feat && o.features) {
       want_feat = true;
       const int v = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(o.features),
@@ -937,6 +1204,10 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     B.newrank = w->newrank;
     B.rowoff = w->rowoff;
     B.tile_sums = w->tile_sums;
+    B.rowstart = w->rowstart;
+    B.rowdeg = w->rowdeg;
+    B.rank = w->rank;
+    B.stile_sums = w->stile_sums;
     B.features = static_cast<uint8_t*>(o.features);
     if (o.labels) {
       if (!g->labels) return SMFG_ERR_INVALID_ARG;
@@ -958,7 +1229,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       if (n > o.node_capacity) n = o.node_capacity;
       if (n > max_n[h]) max_n[h] = n;
       if (h < L) {
-        n = n + n * fanouts[h];
+        n = fanouts[h] < 0 ? g->num_nodes : n + n * fanouts[h];
         if (n > g->num_nodes) n = g->num_nodes;
       }
     }
@@ -984,8 +1255,35 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       P.b[b].edge_capacity = outs[b].edge_capacity[h];
     }
     const int64_t rows = max_n[h];
-    const unsigned row_blocks = blocks_for(rows, (64 / P.d) * (kThreads / 64), kCap);
     const unsigned tile_blocks = blocks_for(rows, kTileRows, kCap);
+    if (wide) {
+      int64_t samples = P.d < 0 ? max_entries : rows * P.d;  // upper bound of E_h
+      if (samples > max_entries) samples = max_entries;
+      const unsigned flat_blocks = blocks_for(samples, kWideTile, kCap);
+      {
+        StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
+        k_count_rows<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
+        k_scan_count_tiles<<<dim3(1, G), kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_SAMPLE, st);
+        k_sample_insert_wide<<<dim3(blocks_for(rows, kThreads / 64, 2 * kCap), G), kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_FLAG, st);
+        k_flag_flat<<<dim3(flat_blocks, G), kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
+        k_scan_flat_tiles<<<dim3(1, G), kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
+        k_assemble_flat<<<dim3(flat_blocks, G), kThreads, 0, st>>>(P);
+      }
+      continue;
+    }
+    const unsigned row_blocks = blocks_for(rows, (64 / P.d) * (kThreads / 64), kCap);
     {
       StageTimer t_(SMFG_STAGE_SAMPLE, st);
       k_sample_insert<<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
@@ -1174,7 +1472,7 @@ const char* smfg_strerror(int code) {
     case SMFG_OK: return "ok";
     case SMFG_ERR_INVALID_ARG: return "invalid argument";
     case SMFG_ERR_NULL_PTR: return "null pointer";
-    case SMFG_ERR_BAD_FANOUT: return "fanout out of range [1, SMFG_MAX_FANOUT]";
+    case SMFG_ERR_BAD_FANOUT: return "fanout is neither SMFG_FANOUT_ALL nor in [1, SMFG_MAX_WIDE_FANOUT]";
     case SMFG_ERR_TOO_MANY_LAYERS: return "number of hops out of range [1, SMFG_MAX_LAYERS]";
     case SMFG_ERR_TOO_MANY_SEEDS: return "more seeds than the workspace or output capacity";
     case SMFG_ERR_OOM: return "out of memory";

@@ -29,7 +29,7 @@ def test_bounds_and_host_validation():
     assert mn == [1024, 16384, 180224, 1081344] and me == [15360, 163840, 901120]
     mn, me = smfg.bounds(1024, (15, 10, 5), 169_000)        # capped by the graph size
     assert mn[-1] == 169_000 and mn[2] == 169_000
-    for bad, code in [((0,), smfg.ERR_BAD_FANOUT), ((33,), smfg.ERR_BAD_FANOUT),
+    for bad, code in [((0,), smfg.ERR_BAD_FANOUT), ((1025,), smfg.ERR_BAD_FANOUT), ((-2,), smfg.ERR_BAD_FANOUT),
                       ((), smfg.ERR_TOO_MANY_LAYERS), ((1,) * 9, smfg.ERR_TOO_MANY_LAYERS)]:
         with pytest.raises(smfg.SmfgError) as ei:
             smfg.bounds(4, bad, 100)
@@ -40,5 +40,6 @@ def test_bounds_and_host_validation():
 
 def test_oracle_and_library_agree_on_bounds():
     import oracle
-    for seeds, fan, n in [(256, (10, 5), 10_000), (4096, (20, 20, 20), 111_000_000), (5, (32,), 20)]:
+    for seeds, fan, n in [(256, (10, 5), 10_000), (4096, (20, 20, 20), 111_000_000), (5, (32,), 20),
+                          (64, (100, 100), 5000), (8, (3, -1, 2), 900), (8, (-1,), 900)]:
         assert tuple(smfg.bounds(seeds, fan, n)) == tuple(oracle.worst_case(seeds, fan, n))

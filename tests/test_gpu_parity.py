@@ -239,7 +239,8 @@ def test_host_argument_errors(tiny):
             fn()
         return ei.value.code
     assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (0, 5), 1, out)) == smfg.ERR_BAD_FANOUT
-    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (33,), 1, out)) == smfg.ERR_BAD_FANOUT
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (1025,), 1, out)) == smfg.ERR_BAD_FANOUT
+    assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (-2,), 1, out)) == smfg.ERR_BAD_FANOUT
     assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (), 1, out)) == smfg.ERR_TOO_MANY_LAYERS
     assert code(lambda: smfg.sample_mfg(gg.g, ws, seeds, (2,) * 9, 1, out)) == smfg.ERR_TOO_MANY_LAYERS
     big = torch.arange(257, dtype=torch.int32, device=DEV)
@@ -338,3 +339,56 @@ def test_mean_aggregate_consumer(dim, dtype):
         # next layer: both sides continue from the GPU's float output cast to the input type
         x_gpu = y[:n_dst].to(x_gpu.dtype).contiguous()
         x_ref = x_gpu.cpu().numpy()
+
+
+@pytest.mark.parametrize("fanouts", [(33,), (64, 3), (5, 100), (100, 100), (-1,), (3, -1), (-1, -1, -1), (40, -1, 7),
+                                     (1024,)])
+def test_wide_fanouts_and_full_neighbourhood(fanouts):
+    """Fanouts above 32 and SMFG_FANOUT_ALL (every neighbour) take the exact-offset path: rows
+    longer than a wave (hub of degree 900, several Floyd rounds), rows shorter than the fanout,
+    an isolated destination."""
+    rng = np.random.default_rng(len(fanouts) * 100 + abs(fanouts[0]))
+    adj = random_simple_graph(3000, 12, rng, hub=900)
+    for extra in (1, 2):                                         # two more long rows
+        for v in rng.choice(np.arange(10, 3000), size=150 * extra, replace=False):
+            if int(v) not in adj[extra]:
+                adj[extra].append(int(v)); adj[int(v)].append(extra)
+    adj[7] = []
+    adj = [sorted(set(u for u in row if u != 7)) for row in adj]
+    indptr, indices = csr_from_adj(adj)
+    feat = rng.standard_normal((3000, 8)).astype(np.float32)
+    gg = GpuGraph(indptr, indices, feat)
+    seeds = np.concatenate([[7, 0, 1, 2], rng.choice(np.arange(8, 3000), size=300, replace=False)]).astype(np.int32)
+    ref = gg.oracle.sample_mfg(seeds, fanouts, 0xABCDEF)
+    assert ref.status == 0
+    m = len(indices)
+    ws = smfg.workspace_create(gg.g, len(seeds), fanouts, node_capacity=3000, sample_capacity=m)
+    out = smfg.alloc_output(gg.g, len(seeds), fanouts, node_capacity=3000, edge_capacity=[m] * len(fanouts))
+    smfg.sample_mfg(gg.g, ws, torch.from_numpy(seeds).to(DEV), fanouts, 0xABCDEF, out)
+    res = fetch(out, len(fanouts))
+    assert_same(res, ref, len(fanouts))
+    if all(d > 0 for d in fanouts):
+        check_mfg(indptr, indices, seeds, fanouts, res["node_ids"], res["indptr"], res["indices"], res["n"], res["e"])
+    # a fast-path call on the same workspace afterwards still works
+    out2 = smfg.alloc_output(gg.g, len(seeds), (4, 3), node_capacity=3000)
+    smfg.sample_mfg(gg.g, ws, torch.from_numpy(seeds).to(DEV), (4, 3), 5, out2)
+    assert_same(fetch(out2, 2), gg.oracle.sample_mfg(seeds, (4, 3), 5), 2)
+
+
+def test_wide_path_capacity_status():
+    rng = np.random.default_rng(3)
+    adj = random_simple_graph(1000, 20, rng)
+    indptr, indices = csr_from_adj(adj)
+    gg = GpuGraph(indptr, indices, None)
+    seeds = rng.choice(1000, size=50, replace=False).astype(np.int32)
+    ref = gg.oracle.sample_mfg(seeds, (-1, -1), 1)
+    e = ref.num_edges
+    ws = smfg.workspace_create(gg.g, 50, (-1, -1), node_capacity=1000, sample_capacity=e[1] - 1)
+    out = smfg.alloc_output(gg.g, 50, (-1, -1), node_capacity=1000, edge_capacity=[len(indices)] * 2)
+    smfg.sample_mfg(gg.g, ws, torch.from_numpy(seeds).to(DEV), (-1, -1), 1, out)
+    assert fetch(out, 2)["status"] == smfg.ST_EDGE_CAPACITY
+    with pytest.raises(smfg.SmfgError):                 # no bound without an explicit sample capacity
+        smfg.workspace_create(gg.g, 50, (-1, -1), node_capacity=1000)
+    ws2 = smfg.workspace_create(gg.g, 50, (-1, -1), node_capacity=1000, sample_capacity=e[1])
+    smfg.sample_mfg(gg.g, ws2, torch.from_numpy(seeds).to(DEV), (-1, -1), 1, out)
+    assert_same(fetch(out, 2), ref, 2)

@@ -36,8 +36,10 @@ MUTATIONS = [
     ("block stores global instead of local ids", "bi[e++] = local_of[g];", "bi[e++] = g;"),
     # not listed: drawing when degree == fanout.  Floyd's rule with k = deg returns the identity
     # order whatever the words are, so that change alters no output.
-    ("degree just above the fanout takes the whole row", "if (deg <= (uint32_t)d)",
-     "if (deg <= (uint32_t)d + 1u)"),
+    ("degree just above the fanout takes the whole row", "if (d == -1 || deg <= (uint32_t)d) {",
+     "if (d == -1 || deg <= (uint32_t)d + 1u) {"),
+    ("fanout -1 treated as fanout 1", "if (d == -1 || deg <= (uint32_t)d) {\n    for",
+     "if (d == -1) d = 1;\n  if (deg <= (uint32_t)d) {\n    for"),
     ("positions ignored: first k neighbours", "indices[a + (int64_t)p[s]]", "indices[a + (int64_t)s]"),
     ("feature row taken by local id", "(int64_t)node_ids[j] * row_stride", "j * row_stride"),
     ("block indptr shifted by one", "bp[i + 1] = (int32_t)e;", "bp[i] = (int32_t)e;"),
@@ -65,6 +67,7 @@ def _pins():
         yield lambda fan=fan: pins.test_invariants_small_graphs(1, fan)
     for L in (1, 2, 3):
         yield lambda L=L: pins.test_full_neighbourhood_equals_bfs(L)
+    yield pins.test_fanout_all_equals_large_fanout_and_bfs
     yield pins.test_consumer_contract_prefix_and_last_block
     yield pins.test_keying_properties
     yield lambda: pins.test_label_slice_is_plain_indexing(np.int32)

@@ -216,6 +216,27 @@ def test_full_neighbourhood_equals_bfs(L):
     assert set(r.node_ids.tolist()) == set(dist)
 
 
+def test_fanout_all_equals_large_fanout_and_bfs():
+    """Fanout -1 (every neighbour; section 5 / Table 6 use "all" next to sampled fanouts) gives the
+    same blocks as any fanout >= max degree, i.e. the BFS construction; mixed with sampled hops the
+    sampled hop is unchanged."""
+    rng = np.random.default_rng(21)
+    adj = random_simple_graph(150, 6, rng, hub=60)
+    maxdeg = max(len(r) for r in adj)
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    seeds = np.array([0, 9, 33], dtype=np.int32)
+    a = orc.sample_mfg(seeds, (-1, -1), 5)
+    b = orc.sample_mfg(seeds, (maxdeg, maxdeg + 7), 6)
+    order, blocks, sizes = _bfs_mfg(adj, seeds.tolist(), 2)
+    assert a.num_nodes == b.num_nodes == sizes and a.node_ids.tolist() == order
+    for h in range(2):
+        assert a.indices[h].tolist() == b.indices[h].tolist() == blocks[h][1]
+    c = orc.sample_mfg(seeds, (3, -1), 5)
+    d = orc.sample_mfg(seeds, (3, maxdeg), 5)
+    assert c.node_ids.tolist() == d.node_ids.tolist() and c.indices[1].tolist() == d.indices[1].tolist()
+
+
 def test_consumer_contract_prefix_and_last_block():
     """Appendix C model listings: dst nodes are a prefix of the src nodes (x_target = x[:size[1]])
     and the block consumed last has the batch size as its dst count."""
