@@ -139,14 +139,16 @@ def main():
     L = len(w.fanouts)
     g = smfg.graph_create(graph.indptr, graph.indices, feat)
     pipe = None
+    wide = any(d < 0 or d > smfg.MAX_FANOUT for d in w.fanouts)
+    scap = min(graph.num_edges, (1 << 30) - 1) if wide else 0   # a hop never has more samples than the graph has edges
     if args.pipeline:
         from paper_2110_08450_amd.pipeline import BatchPipeline
-        pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G)
+        pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G, sample_capacity=scap)
         S, streams, wss, outs = 2, [pipe.s_sample, pipe.s_gather], pipe.wss, pipe.outs
     else:
         S = max(1, args.streams)
         streams = [torch.cuda.Stream() for _ in range(S)]
-        wss = [[smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
+        wss = [[smfg.workspace_create(g, w.batch_size, w.fanouts, 0, scap) for _ in range(G)] for _ in range(S)]
         outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
     row_bytes = g.row_bytes
 

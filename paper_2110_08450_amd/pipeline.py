@@ -18,12 +18,12 @@ from . import binding as smfg
 
 class BatchPipeline:
     def __init__(self, g: smfg.Graph, fanouts: Sequence[int], batch_size: int, batches_per_set: int = 8,
-                 node_capacity: Optional[int] = None, depth: int = 2):
+                 node_capacity: Optional[int] = None, depth: int = 2, sample_capacity: int = 0):
         self.g, self.fanouts = g, tuple(fanouts)
         self.G = max(1, min(batches_per_set, smfg.MAX_BATCHES))
         self.depth = depth
         cap = 0 if node_capacity is None else node_capacity
-        self.wss = [[smfg.workspace_create(g, batch_size, self.fanouts, cap) for _ in range(self.G)]
+        self.wss = [[smfg.workspace_create(g, batch_size, self.fanouts, cap, sample_capacity) for _ in range(self.G)]
                     for _ in range(depth)]
         self.outs = [[smfg.alloc_output(g, batch_size, self.fanouts, node_capacity) for _ in range(self.G)]
                      for _ in range(depth)]

@@ -248,6 +248,12 @@ WORKLOADS = {
     # Shaped like ogbn-products.
     "large": Workload("large", 2_450_000, 124_000_000, 17_000.0, None, 100, torch.float16,
                       (15, 10, 5), 1024, 0.0, 0.08, None, 1003),
+    # products-shaped graph with fanouts beyond 32 and with full neighbourhoods (Table 6 compares
+    # fanouts (20,20,20), (100,100,100) and "all" for inference).
+    "large_wide": Workload("large_wide", 2_450_000, 124_000_000, 17_000.0, None, 100, torch.float16,
+                           (100, 100), 1024, 0.08, 0.02, None, 1003),
+    "large_all": Workload("large_all", 2_450_000, 124_000_000, 17_000.0, None, 100, torch.float16,
+                          (-1, -1), 256, 0.08, 0.005, None, 1003),
     # Shaped like ogbn-papers100M, training fanouts.
     "papers": Workload("papers", 111_000_000, 3_200_000_000, 100_000.0, 3.5, 128, torch.float16,
                        (15, 10, 5), 1024, 0.0, 0.011, None, 1004),
