@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # HBM bytes per k_gather launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (profiles/papers_kernel_trace_and_hbm_traffic.txt), scaled by what the same counters read
 # for the identity copy of known size; keyed by (workload, batches per launch).
-MEASURED_GATHER_TRAFFIC_BYTES = {("papers", 8): 3.613e9}
+MEASURED_GATHER_TRAFFIC_BYTES = {("papers", 8): 3.610e9}
 
 
 def log(*a):
