@@ -93,8 +93,8 @@ def cpu_baseline(w, graph, feat, batches, keys, budget_s, threads, gpu_check):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=512)
-    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--steps", type=int, default=4096)
+    ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="papers")
     ap.add_argument("--batches-per-call", type=int, default=8)
     ap.add_argument("--streams", type=int, default=1,

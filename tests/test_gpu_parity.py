@@ -392,3 +392,43 @@ def test_wide_path_capacity_status():
     ws2 = smfg.workspace_create(gg.g, 50, (-1, -1), node_capacity=1000, sample_capacity=e[1])
     smfg.sample_mfg(gg.g, ws2, torch.from_numpy(seeds).to(DEV), (-1, -1), 1, out)
     assert_same(fetch(out, 2), ref, 2)
+
+
+def test_launch_set_replays_from_a_hip_graph(tiny):
+    """A launch set allocates nothing and never synchronises, so it can be captured into a HIP
+    graph; every replay (with eager work and synchronisation in between) must give the oracle's
+    result again, the workspace resetting itself each time."""
+    w, gg, batches = tiny
+    L = len(w.fanouts)
+    G = 3
+    wss = [smfg.workspace_create(gg.g, w.batch_size, w.fanouts) for _ in range(G)]
+    outs = [smfg.alloc_output(gg.g, w.batch_size, w.fanouts) for _ in range(G)]
+    seeds = [torch.empty(w.batch_size, dtype=torch.int32, device=DEV) for _ in range(G)]
+    keys = [synth.batch_rng_key(w, b) for b in range(G)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture
+        for b in range(G):
+            seeds[b].copy_(batches[b].to(DEV))
+        smfg.sample_mfg_many(gg.g, wss, seeds, w.fanouts, keys, outs, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        smfg.sample_mfg_many(gg.g, wss, seeds, w.fanouts, keys, outs, stream=torch.cuda.current_stream())
+    refs = {}
+    for rep in range(4):
+        # new seeds in the same buffers for replays 2 and 3: the captured pointers stay valid
+        shift = rep % 2
+        for b in range(G):
+            seeds[b].copy_(batches[(b + shift) % len(batches)].to(DEV))
+        for o in outs:                                  # eager work between the replays
+            o.node_ids.fill_(-7)
+            o.features.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for b in range(G):
+            src = (b + shift) % len(batches)
+            ref = refs.setdefault((src, b), gg.oracle.sample_mfg(batches[src].numpy(), w.fanouts, keys[b]))
+            assert_same(fetch(outs[b], L), ref, L)
