@@ -1,0 +1,76 @@
+// libsmfg feature gather xs = x[ids] (Listing 1).
+#ifndef SMFG_KERNELS_GATHER_H_
+#define SMFG_KERNELS_GATHER_H_
+
+#include "device_common.h"
+
+namespace smfg_dev {
+
+// Rows are moved as vectors of sizeof(V) bytes.  A block copies kGatherRows consecutive output
+// rows and exits: many short-lived blocks reach a higher copy rate on this chip than a persistent
+// grid-stride loop.  Inside a block the output chunk is addressed as one flat vector array, so
+// stores are fully coalesced and the lanes that share a row read one contiguous span of it.
+constexpr int kGatherRows = 32;
+template <typename V>
+__device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, int64_t row_stride,
+                                            uint32_t vec_per_row, const int32_t* __restrict__ ids,
+                                            int64_t n, uint8_t* __restrict__ out) {
+  constexpr int U = 2;
+  __shared__ int64_t row_byte[kGatherRows];  // byte offset of each source row
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
+  if (r0 >= n) return;
+  const uint32_t rows = static_cast<uint32_t>(n - r0 < kGatherRows ? n - r0 : kGatherRows);
+  const uint32_t cnt = rows * vec_per_row;
+  if (threadIdx.x < kGatherRows)
+    row_byte[threadIdx.x] = threadIdx.x < rows ? static_cast<int64_t>(ids[r0 + threadIdx.x]) * row_stride : 0;
+  __syncthreads();
+  V* __restrict__ o = reinterpret_cast<V*>(out) + static_cast<uint64_t>(r0) * vec_per_row;
+  uint32_t base = threadIdx.x;
+  // full rounds: U independent row reads in flight per thread, then the U stores
+  for (; base + (U - 1) * kThreads < cnt; base += kThreads * U) {
+    V val[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t idx = base + u * kThreads;
+      const uint32_t jrow = idx / vec_per_row;
+      const uint32_t c = idx - jrow * vec_per_row;
+      val[u] = __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(val[u], o + base + u * kThreads);
+  }
+  for (; base < cnt; base += kThreads) {
+    const uint32_t jrow = base / vec_per_row;
+    const uint32_t c = base - jrow * vec_per_row;
+    __builtin_nontemporal_store(
+        __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c), o + base);
+  }
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename V>
+__global__ void __launch_bounds__(kThreads) k_gather(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  int64_t n = B.counts[P.L];
+  if (n > B.node_capacity) n = B.node_capacity;
+  gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), B.node_ids, n,
+                 B.features);
+}
+
+template <typename V>
+__global__ void __launch_bounds__(kThreads) k_gather_plain(const uint8_t* feat, int64_t row_bytes,
+                                                           int64_t row_stride, const int32_t* ids,
+                                                           const int64_t* num_rows, int64_t max_rows,
+                                                           uint8_t* out) {
+  int64_t n = *num_rows;
+  if (n > max_rows) n = max_rows;
+  if (n < 0) n = 0;
+  gather_rows<V>(feat, row_stride, static_cast<uint32_t>(row_bytes / sizeof(V)), ids, n, out);
+}
+
+}  // namespace smfg_dev
+
+#endif  // SMFG_KERNELS_GATHER_H_

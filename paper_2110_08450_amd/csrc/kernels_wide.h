@@ -1,0 +1,237 @@
+// libsmfg wide path: fanouts above SMFG_MAX_FANOUT and SMFG_FANOUT_ALL, samples at exact block offsets.
+#ifndef SMFG_KERNELS_WIDE_H_
+#define SMFG_KERNELS_WIDE_H_
+
+#include "device_common.h"
+
+namespace smfg_dev {
+
+// Samples sit at their exact block offsets (pos = block indptr[i] + s), so a count + scan pass
+// comes first and the later passes walk the samples flat, four consecutive samples per thread.
+constexpr int kWideTile = 4 * kThreads;  // samples per flat tile
+
+// Degree, sample count and row start per destination; in-tile scan of the sample counts.
+__global__ void __launch_bounds__(kThreads) k_count_rows(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int d = P.d;
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const int i = tile * kTileRows + threadIdx.x;
+    uint32_t k = 0;
+    if (i < n) {
+      const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
+      const int64_t a = P.indptr[v];
+      const uint32_t deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
+      k = (d < 0 || deg <= static_cast<uint32_t>(d)) ? deg : static_cast<uint32_t>(d);
+      B.rowstart[i] = a;
+      B.rowdeg[i] = deg;
+      B.rowk[i] = static_cast<int32_t>(k);
+    }
+    unsigned long long total;
+    const unsigned long long pre = block_exscan(k, lds, total);
+    if (i < n) B.rowoff[i] = static_cast<int32_t>(pre);
+    if (threadIdx.x == 0) B.tile_sums[tile] = total;
+    __syncthreads();
+  }
+}
+
+// Exclusive scan of the per-tile sample counts; E_h and its capacity checks.
+__global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  unsigned long long carry = 0;
+  for (int t0 = 0; t0 < tiles; t0 += kThreads) {
+    const int t = t0 + threadIdx.x;
+    const unsigned long long x = t < tiles ? B.tile_sums[t] : 0ull;
+    unsigned long long total;
+    const unsigned long long ex = block_exscan(x, lds, total);
+    if (t < tiles) B.tile_sums[t] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    const bool fits = carry <= static_cast<unsigned long long>(B.edge_capacity) &&
+                      carry <= static_cast<unsigned long long>(B.lostto_entries);
+    B.counts[P.L + 1 + P.h] = static_cast<int64_t>(carry);
+    if (fits) B.blk_indptr[n] = static_cast<int32_t>(carry);
+    else set_status(B, P.L, SMFG_ST_EDGE_CAPACITY);
+  }
+}
+
+// One wave per destination; lane l of round r owns slot s = 64 r + l.
+__global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P) {
+  __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  uint32_t* picks = picks_lds[wave];
+  const int waves_total = gridDim.x * (kThreads / 64);
+  for (int i = blockIdx.x * (kThreads / 64) + wave; i < n; i += waves_total) {
+    const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
+    const int64_t a = B.rowstart[i];
+    const uint32_t deg = static_cast<uint32_t>(B.rowdeg[i]);
+    const uint32_t k = static_cast<uint32_t>(B.rowk[i]);
+    const uint32_t base = static_cast<uint32_t>(B.tile_sums[i / kTileRows]) + static_cast<uint32_t>(B.rowoff[i]);
+    if (lane == 0) B.blk_indptr[i] = static_cast<int32_t>(base);
+    const bool floyd = deg > k;  // only then are positions drawn (k = fanout <= SMFG_MAX_WIDE_FANOUT)
+    for (uint32_t s0 = 0; s0 < k; s0 += 64) {
+      const uint32_t s = s0 + static_cast<uint32_t>(lane);
+      const bool active = s < k;
+      uint32_t p = s;  // whole row in CSR order when nothing is drawn
+      if (floyd) {
+        uint32_t t = 0, j = 0;
+        if (active) {
+          const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), s >> 2, B.key0, B.key1, s & 3u);
+          j = deg - k + s;
+          t = __umulhi(w, j + 1u);  // index in [0, j]
+        }
+        // Floyd's rule slot by slot; the array set is picks[0, s0) in LDS plus the lanes of this round
+        const uint32_t round = k - s0 < 64u ? k - s0 : 64u;
+        for (uint32_t q = 0; q < round; ++q) {
+          const uint32_t tq = __shfl(t, static_cast<int>(q), 64);
+          bool hit = static_cast<uint32_t>(lane) < q && p == tq;
+          for (uint32_t l = static_cast<uint32_t>(lane); l < s0; l += 64) hit = hit || picks[l] == tq;
+          const bool any = __ballot(hit) != 0ull;
+          if (static_cast<uint32_t>(lane) == q) p = any ? j : tq;
+        }
+        if (active) picks[s] = p;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // later rounds read all lanes' picks
+        __builtin_amdgcn_wave_barrier();
+      }
+      if (active) {
+        const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
+        const uint32_t pos = base + s;
+        uint32_t slot;
+        bool full;
+        const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
+        if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
+        uint32_t e = prev;  // see k_sample_insert for the three cases
+        if (prev > (kPend | pos)) {
+          e = kSlot | slot;
+          if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
+        }
+        B.ent[pos] = e;
+        B.gsrc[pos] = static_cast<int32_t>(g);
+      }
+    }
+  }
+}
+
+// Flat over the samples: first appearances, their in-tile ranks, per-tile totals.
+__global__ void __launch_bounds__(kThreads) k_flag_flat(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) {
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < B.lostto_entries;
+         q += static_cast<int64_t>(gridDim.x) * kThreads)
+      B.lostto[q] = 0u;
+    return;
+  }
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
+    uint32_t first[4];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      first[u] = 0;
+      const uint32_t pos = p0 + u;
+      if (pos < E) {
+        const uint32_t lost = B.lostto[pos];
+        if (lost != 0u) {
+          B.ent[pos] = lost;
+          B.lostto[pos] = 0u;
+        } else {
+          first[u] = (B.ent[pos] & kTagMask) == kSlot ? 1u : 0u;
+        }
+      }
+      mine += first[u];
+    }
+    unsigned long long total;
+    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (p0 + u < E) B.rank[p0 + u] = pre;
+      pre += first[u];
+    }
+    if (threadIdx.x == 0) B.stile_sums[tile] = total;
+    __syncthreads();
+  }
+}
+
+// Exclusive scan of the per-tile counts of new nodes; n_{h+1} and its capacity check.
+__global__ void __launch_bounds__(kThreads) k_scan_flat_tiles(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  unsigned long long carry = 0;
+  for (uint32_t t0 = 0; t0 < tiles; t0 += kThreads) {
+    const uint32_t t = t0 + threadIdx.x;
+    const unsigned long long x = t < tiles ? B.stile_sums[t] : 0ull;
+    unsigned long long total;
+    const unsigned long long ex = block_exscan(x, lds, total);
+    if (t < tiles) B.stile_sums[t] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    const int64_t nodes = static_cast<int64_t>(n) + static_cast<int64_t>(carry);
+    B.counts[P.h + 1] = nodes;
+    if (nodes > B.node_capacity) set_status(B, P.L, SMFG_ST_NODE_CAPACITY);
+  }
+}
+
+// Flat over the samples: final local ids -> block indices; first appearances publish themselves.
+__global__ void __launch_bounds__(kThreads) k_assemble_flat(const Launch P) {
+  const BatchCtx& B = P.b[blockIdx.y];
+  if (status_of(B, P.L) != 0) return;
+  const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const bool last = P.h == P.L - 1;
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint32_t tpre = n + static_cast<uint32_t>(B.stile_sums[tile]);
+    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t pos = p0 + u;
+      if (pos >= E) continue;
+      const uint32_t e = B.ent[pos];
+      const uint32_t tag = e & kTagMask;
+      uint32_t local = e;
+      if (tag == kSlot) {
+        local = tpre + B.rank[pos];
+        const uint32_t g = static_cast<uint32_t>(B.gsrc[pos]);
+        B.node_ids[local] = static_cast<int32_t>(g);
+        if (!last) B.table[e & ~kTagMask] = (static_cast<uint64_t>(g) << 32) | local;
+      } else if (tag != 0u) {  // kPend: same node as the sample at position q < pos
+        uint32_t q = e & ~kTagMask;
+        for (;;) {
+          const uint32_t eq = B.ent[q];
+          if ((eq & kTagMask) == kSlot) {  // q is the node's first appearance
+            local = n + static_cast<uint32_t>(B.stile_sums[q / kWideTile]) + B.rank[q];
+            break;
+          }
+          const uint32_t nxt = eq & ~kTagMask;  // strictly smaller position
+          if (nxt >= q) break;                  // cannot happen; guards the loop
+          q = nxt;
+        }
+      }
+      B.blk_indices[pos] = static_cast<int32_t>(local);
+    }
+  }
+}
+
+}  // namespace smfg_dev
+
+#endif  // SMFG_KERNELS_WIDE_H_

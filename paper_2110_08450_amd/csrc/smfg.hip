@@ -1,4 +1,7 @@
 // libsmfg: sampled mini-batch preparation on gfx950 (MI355X).  Implements include/smfg.h.
+// This file is the host side (handles, validation, launch sequences); the kernels live in
+// device_common.h (launch parameters, Philox, dedup table), kernels_fast.h (fanouts up to 32),
+// kernels_wide.h (larger fanouts, full neighbourhoods), kernels_gather.h, kernels_aggregate.h.
 //
 // One hop h of one batch is four launches (all batches of a call share each launch through
 // blockIdx.y):
@@ -36,789 +39,15 @@
 
 #include "smfg.h"
 
+#include "device_common.h"
+#include "kernels_aggregate.h"
+#include "kernels_fast.h"
+#include "kernels_gather.h"
+#include "kernels_wide.h"
+
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kTileRows = 256;              // destinations per scan tile
-constexpr uint32_t kPend = 0x80000000u;     // table value / entry tag: a position of this hop
-constexpr uint32_t kSlot = 0x40000000u;     // entry tag: index of the sample's table slot
-constexpr uint32_t kTagMask = 0xC0000000u;
-constexpr uint64_t kEmpty = ~0ull;
-constexpr uint32_t kMaxProbes = 4096;      // longest probe run before the table counts as full
-
-struct BatchCtx {
-  const int32_t* seeds;
-  int64_t* counts;       // [2L+2]
-  uint64_t* table;
-  int32_t* node_ids;
-  uint32_t* ent;         // per (destination, s): final local id | kSlot+slot (owner) | kPend+position
-  uint32_t* lostto;      // per (destination, s): 0, or kPend+position of the sample that displaced it
-  int64_t lostto_entries;
-  int32_t* gsrc;         // per (destination, s): global id of the sampled neighbour
-  int32_t* rowk;         // samples per destination
-  uint32_t* rowmask;     // first-appearance bits per destination
-  int32_t* newrank;      // new nodes of the tile before this destination's first new node
-  int32_t* rowoff;       // samples of the tile before this destination
-  uint64_t* tile_sums;   // per tile: (edges << 32 | new nodes), later their exclusive scan
-  int64_t* rowstart;     // wide path: first CSR position of the destination's row
-  int32_t* rowdeg;       // wide path: degree of the destination
-  uint32_t* rank;        // wide path: new nodes of the sample's tile before this sample
-  uint64_t* stile_sums;  // wide path: per sample tile, new nodes, later their exclusive scan
-  int32_t* blk_indptr;   // hop h
-  int32_t* blk_indices;  // hop h
-  uint8_t* features;
-  uint8_t* labels;       // [num_seeds x label bytes] or null
-  int64_t edge_capacity; // hop h
-  int32_t node_capacity;
-  int32_t num_seeds;
-  uint32_t key0, key1;
-  uint32_t table_shift;  // slot = hash >> shift
-  uint32_t table_mask;
-};
-
-struct Launch {
-  const int64_t* indptr;
-  const int32_t* indices;
-  const uint8_t* feat;
-  const uint8_t* labels;  // y, label_bytes per node, or null
-  int64_t row_bytes;
-  int64_t row_stride;
-  int64_t num_nodes;
-  int32_t label_bytes;
-  int32_t L;       // hops of this call (counts layout)
-  int32_t h;       // current hop
-  int32_t d;       // its fanout
-  int32_t G;       // batches
-  BatchCtx b[SMFG_MAX_BATCHES];
-};
-
-__device__ __forceinline__ int64_t status_of(const BatchCtx& B, int L) {
-  return __hip_atomic_load(&B.counts[2 * L + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ void set_status(const BatchCtx& B, int L, int64_t code) {
-  unsigned long long* p = reinterpret_cast<unsigned long long*>(&B.counts[2 * L + 1]);
-  atomicCAS(p, 0ull, static_cast<unsigned long long>(code));
-}
-
-// ---- Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) -------------------------------------
-// Returns word `w` (0..3) of the block with counter (c0, c1, c2, 0) and key (k0, k1).
-__device__ __forceinline__ uint32_t philox_word(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t k0,
-                                                uint32_t k1, uint32_t w) {
-  constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
-  uint32_t c3 = 0u;
-#pragma unroll
-  for (int r = 0; r < 10; ++r) {
-    const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-    const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
-    const uint32_t n0 = hi1 ^ c1 ^ k0;
-    const uint32_t n2 = hi0 ^ c3 ^ k1;
-    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
-  }
-  return w == 0 ? c0 : (w == 1 ? c1 : (w == 2 ? c2 : c3));
-}
-
-// ---- dedup table ----------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t hash_slot(uint32_t key, uint32_t shift) {
-  return (key * 0x9E3779B1u) >> shift;
-}
-
-// Inserts key with value `val`, or lowers the stored value to `val`.  Returns the value that
-// stood in the table just before this sample's own update took effect (0xFFFFFFFF when the key
-// was new) and the slot in `slot`.  The first access of a probe is the compare-and-swap itself:
-// on the common paths (key new, or key present with a smaller value) it is the only access.
-// If the returned value is larger than `val`, this call is the one and only update that
-// replaced exactly that value.
-__device__ __forceinline__ uint32_t table_insert_min(const BatchCtx& B, uint32_t key, uint32_t val,
-                                                     uint32_t& slot, bool& full) {
-  unsigned long long* T = reinterpret_cast<unsigned long long*>(B.table);
-  const unsigned long long mine = (static_cast<unsigned long long>(key) << 32) | val;
-  uint32_t s = hash_slot(key, B.table_shift);
-  full = false;
-  // The table has at least two slots per node of capacity, so a probe run this long only occurs
-  // when far more distinct nodes arrive than the capacity allows: report the table as full.
-  const uint32_t max_probes = B.table_mask < kMaxProbes ? B.table_mask + 1u : kMaxProbes;
-  for (uint32_t probes = 0; probes < max_probes; ++probes) {
-    unsigned long long old = atomicCAS(&T[s], kEmpty, mine);
-    if (old == kEmpty) {
-      slot = s;
-      return 0xFFFFFFFFu;
-    }
-    if (static_cast<uint32_t>(old >> 32) == key) {
-      slot = s;
-      if (static_cast<uint32_t>(old) > val) old = atomicMin(&T[s], mine);
-      return static_cast<uint32_t>(old);
-    }
-    s = (s + 1) & B.table_mask;
-  }
-  full = true;
-  slot = 0;
-  return 0u;
-}
-
-// ---- kernels --------------------------------------------------------------------------------
-
-__global__ void __launch_bounds__(kThreads) k_clear(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
-  const size_t n = static_cast<size_t>(B.table_mask) + 1;
-  for (size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x; i < n;
-       i += static_cast<size_t>(gridDim.x) * kThreads)
-    B.table[i] = kEmpty;
-  if (blockIdx.x == 0) {
-    const int m = 2 * P.L + 2;
-    for (int q = threadIdx.x; q < m; q += kThreads) B.counts[q] = (q == 0) ? B.num_seeds : 0;
-  }
-}
-
-// M starts with the destination nodes of hop 0 in the order given (procedure OneHopMFG).
-__global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
-  for (int i = blockIdx.x * kThreads + threadIdx.x; i < B.num_seeds; i += gridDim.x * kThreads) {
-    const int32_t v = B.seeds[i];
-    if (v < 0 || static_cast<int64_t>(v) >= P.num_nodes) {
-      set_status(B, P.L, SMFG_ST_SEED_OUT_OF_RANGE);
-      continue;
-    }
-    uint32_t slot;
-    bool full;
-    const uint32_t prev = table_insert_min(B, static_cast<uint32_t>(v), static_cast<uint32_t>(i), slot, full);
-    if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
-    else if (prev != 0xFFFFFFFFu) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
-    B.node_ids[i] = v;
-    if (B.labels) {  // ys = y[ids[:batch_size]] (Listing 1): the seeds are the first ids
-      const uint8_t* src = P.labels + static_cast<int64_t>(v) * P.label_bytes;
-      uint8_t* dst = B.labels + static_cast<int64_t>(i) * P.label_bytes;
-      switch (P.label_bytes) {
-        case 8: *reinterpret_cast<uint64_t*>(dst) = *reinterpret_cast<const uint64_t*>(src); break;
-        case 4: *reinterpret_cast<uint32_t*>(dst) = *reinterpret_cast<const uint32_t*>(src); break;
-        case 2: *reinterpret_cast<uint16_t*>(dst) = *reinterpret_cast<const uint16_t*>(src); break;
-        default: *dst = *src; break;
-      }
-    }
-  }
-}
-
-// d lanes cooperate on one destination, lane s of the group owns slot s; a wave holds
-// floor(64 / d) groups (its last 64 mod d lanes idle).
-__global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int d = P.d;
-  const int lane = threadIdx.x & 63;
-  const int per_wave = 64 / d;                 // destinations per wave
-  const int per_block = per_wave * (kThreads / 64);
-  const int grp = lane / d;
-  const int s = lane - grp * d;
-  const bool lane_used = grp < per_wave;
-  const int gbase = grp * d;                   // first lane of the group within the wave
-  const unsigned long long gmask = (1ull << d) - 1ull;
-  const int row_in_block = (threadIdx.x >> 6) * per_wave + grp;
-
-  for (int i0 = blockIdx.x * per_block; i0 < n; i0 += gridDim.x * per_block) {
-    const int i = i0 + row_in_block;
-    const bool row = lane_used && i < n;
-    uint32_t v = 0, deg = 0;
-    int64_t a = 0;
-    if (row) {
-      v = static_cast<uint32_t>(B.node_ids[i]);
-      a = P.indptr[v];
-      deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
-    }
-    const bool floyd = row && deg > static_cast<uint32_t>(d);
-    const uint32_t k = floyd ? static_cast<uint32_t>(d) : deg;
-    uint32_t p = static_cast<uint32_t>(s);  // whole row in CSR order when deg <= d
-    uint32_t t = 0, j = 0;
-    if (floyd) {
-      const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), static_cast<uint32_t>(s) >> 2,
-                                     B.key0, B.key1, static_cast<uint32_t>(s) & 3u);
-      j = deg - static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
-      t = __umulhi(w, j + 1u);  // index in [0, j]
-    }
-    // Floyd's subset algorithm, resolved slot by slot: pick t_s unless an earlier slot holds it,
-    // then pick j_s.  The membership test is a linear search over the lanes (the array set).
-    if (__any(floyd)) {
-      for (int q = 0; q < d; ++q) {
-        const uint32_t tq = __shfl(t, gbase + q, 64);
-        const bool hit = floyd && s < q && p == tq;
-        const unsigned long long bal = (__ballot(hit) >> gbase) & gmask;
-        if (floyd && s == q) p = bal ? j : tq;
-      }
-    }
-    if (row && static_cast<uint32_t>(s) < k) {
-      const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
-      const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
-      uint32_t slot;
-      bool full;
-      const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
-      if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
-      // prev < kPend      : a node known before this hop, prev is its final local id
-      // prev < kPend|pos  : an earlier sample of this hop holds the node: keep it as a pointer
-      // prev > kPend|pos  : this sample now holds the node; it displaced the sample at prev
-      //                     (unless the node was new), which is told so through lostto
-      uint32_t e = prev;
-      if (prev > (kPend | pos)) {
-        e = kSlot | slot;
-        if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
-      }
-      B.ent[pos] = e;
-      B.gsrc[pos] = static_cast<int32_t>(g);
-    }
-    if (row && s == 0) B.rowk[i] = static_cast<int32_t>(k);
-  }
-}
-
-// Exclusive scan over a block of kThreads values; returns the exclusive prefix, total in `total`.
-__device__ __forceinline__ unsigned long long block_exscan(unsigned long long x, unsigned long long* lds,
-                                                            unsigned long long& total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  unsigned long long inc = x;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned long long y = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += y;
-  }
-  __syncthreads();
-  if (lane == 63) lds[wave] = inc;
-  __syncthreads();
-  unsigned long long base = 0, tot = 0;
-#pragma unroll
-  for (int w = 0; w < kThreads / 64; ++w) {
-    const unsigned long long v = lds[w];
-    if (w < wave) base += v;
-    tot += v;
-  }
-  total = tot;
-  return base + inc - x;
-}
-
-// (destination, slot) of the idx-th padded sample of a tile: idx = r * d + s.
-struct DivD {
-  uint64_t inv;  // ceil(2^32 / d); the quotient is exact for idx < 2^27
-  uint32_t d;
-  __device__ __forceinline__ explicit DivD(uint32_t d_) : inv((0xFFFFFFFFull / d_) + 1ull), d(d_) {}
-  __device__ __forceinline__ void split(uint32_t idx, uint32_t& r, uint32_t& s) const {
-    r = static_cast<uint32_t>((static_cast<uint64_t>(idx) * inv) >> 32);
-    s = idx - r * d;
-  }
-};
-
-// One block per tile of kTileRows destinations.  The padded samples of a tile are one contiguous
-// span of ent / lostto, read flat and coalesced.
-__global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
-  __shared__ int k_lds[kTileRows];
-  __shared__ unsigned int mask_lds[kTileRows];
-  static_assert(kTileRows == kThreads, "one row per thread");
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) {
-    // a failed sample_insert may have left displacement notes behind: wipe them all
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < B.lostto_entries;
-         q += static_cast<int64_t>(gridDim.x) * kThreads)
-      B.lostto[q] = 0u;
-    return;
-  }
-  const int n = static_cast<int>(B.counts[P.h]);
-  const uint32_t d = static_cast<uint32_t>(P.d);
-  const DivD div(d);
-  const int tiles = (n + kTileRows - 1) / kTileRows;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const int i0 = tile * kTileRows;
-    const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
-    const int tr = threadIdx.x;
-    __syncthreads();
-    k_lds[tr] = tr < nrows ? B.rowk[i0 + tr] : 0;
-    mask_lds[tr] = 0u;
-    __syncthreads();
-    const uint32_t pos0 = static_cast<uint32_t>(i0) * d;
-    const uint32_t cnt = static_cast<uint32_t>(nrows) * d;
-    constexpr int U = 4;
-    for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
-      uint32_t lost[U], e[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const uint32_t idx = base + u * kThreads;
-        lost[u] = idx < cnt ? B.lostto[pos0 + idx] : 0u;
-        e[u] = idx < cnt ? B.ent[pos0 + idx] : 0u;
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const uint32_t idx = base + u * kThreads;
-        if (idx < cnt) {
-          uint32_t r, sl;
-          div.split(idx, r, sl);
-          if (sl < static_cast<uint32_t>(k_lds[r])) {
-            if (lost[u] != 0u) {  // displaced by the sample at lost[u]: follow it later
-              B.ent[pos0 + idx] = lost[u];
-              B.lostto[pos0 + idx] = 0u;
-            } else if ((e[u] & kTagMask) == kSlot) {
-              atomicOr(&mask_lds[r], 1u << sl);
-            }
-          }
-        }
-      }
-    }
-    __syncthreads();
-    const int k = k_lds[tr];
-    const uint32_t m = mask_lds[tr];
-    const unsigned long long x = (static_cast<unsigned long long>(k) << 32) | static_cast<unsigned long long>(__popc(m));
-    unsigned long long total;
-    const unsigned long long pre = block_exscan(x, lds, total);
-    if (tr < nrows) {
-      B.rowmask[i0 + tr] = m;
-      B.rowoff[i0 + tr] = static_cast<int32_t>(pre >> 32);
-      B.newrank[i0 + tr] = static_cast<int32_t>(pre & 0xFFFFFFFFull);
-    }
-    if (tr == 0) B.tile_sums[tile] = total;
-  }
-}
-
-__global__ void __launch_bounds__(kThreads) k_scan_tiles(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int tiles = (n + kTileRows - 1) / kTileRows;
-  unsigned long long carry = 0;
-  for (int t0 = 0; t0 < tiles; t0 += kThreads) {
-    const int t = t0 + threadIdx.x;
-    const unsigned long long x = t < tiles ? B.tile_sums[t] : 0ull;
-    unsigned long long total;
-    const unsigned long long ex = block_exscan(x, lds, total);
-    if (t < tiles) B.tile_sums[t] = carry + ex;
-    carry += total;
-  }
-  if (threadIdx.x == 0) {
-    const int64_t edges = static_cast<int64_t>(carry >> 32);
-    const int64_t nodes = static_cast<int64_t>(n) + static_cast<int64_t>(carry & 0xFFFFFFFFull);
-    B.counts[P.L + 1 + P.h] = edges;
-    B.counts[P.h + 1] = nodes;
-    B.blk_indptr[n] = static_cast<int32_t>(edges);
-    if (nodes > B.node_capacity) set_status(B, P.L, SMFG_ST_NODE_CAPACITY);
-    else if (edges > B.edge_capacity) set_status(B, P.L, SMFG_ST_EDGE_CAPACITY);
-  }
-}
-
-// One block per tile of kTileRows destinations; samples are walked flat like in k_flag_rows.
-__global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
-  __shared__ int k_lds[kTileRows];
-  __shared__ unsigned int mask_lds[kTileRows];
-  __shared__ unsigned int off_lds[kTileRows];   // global edge offset of the destination
-  __shared__ unsigned int rank_lds[kTileRows];  // local id of the destination's first new node
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const uint32_t d = static_cast<uint32_t>(P.d);
-  const DivD div(d);
-  const bool last = P.h == P.L - 1;  // nodes found in the last hop are never looked up again
-  const int tiles = (n + kTileRows - 1) / kTileRows;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const int i0 = tile * kTileRows;
-    const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
-    const int tr = threadIdx.x;
-    const unsigned long long tpre = B.tile_sums[tile];
-    __syncthreads();
-    if (tr < nrows) {
-      const uint32_t off = static_cast<uint32_t>(tpre >> 32) + static_cast<uint32_t>(B.rowoff[i0 + tr]);
-      k_lds[tr] = B.rowk[i0 + tr];
-      mask_lds[tr] = B.rowmask[i0 + tr];
-      off_lds[tr] = off;
-      rank_lds[tr] = static_cast<uint32_t>(n) + static_cast<uint32_t>(tpre & 0xFFFFFFFFull) +
-                     static_cast<uint32_t>(B.newrank[i0 + tr]);
-      B.blk_indptr[i0 + tr] = static_cast<int32_t>(off);
-    } else {
-      k_lds[tr] = 0;
-    }
-    __syncthreads();
-    const uint32_t pos0 = static_cast<uint32_t>(i0) * d;
-    const uint32_t cnt = static_cast<uint32_t>(nrows) * d;
-    constexpr int U = 4;
-    for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
-      uint32_t e[U], g[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const uint32_t idx = base + u * kThreads;
-        e[u] = idx < cnt ? B.ent[pos0 + idx] : 0u;
-        g[u] = idx < cnt ? static_cast<uint32_t>(B.gsrc[pos0 + idx]) : 0u;
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const uint32_t idx = base + u * kThreads;
-        if (idx >= cnt) continue;
-        uint32_t r, sl;
-        div.split(idx, r, sl);
-        if (sl >= static_cast<uint32_t>(k_lds[r])) continue;
-        const uint32_t tag = e[u] & kTagMask;
-        uint32_t local = e[u];
-        if (tag == kSlot) {  // first appearance: rank among the new nodes of this hop
-          local = rank_lds[r] + __popc(mask_lds[r] & ((1u << sl) - 1u));
-          B.node_ids[local] = static_cast<int32_t>(g[u]);
-          if (!last) B.table[e[u] & ~kTagMask] = (static_cast<uint64_t>(g[u]) << 32) | local;
-        } else if (tag != 0u) {  // kPend: same node as the sample at position q < own position
-          uint32_t q = e[u] & ~kTagMask;
-          for (;;) {
-            const uint32_t qi = q / d, qs = q - qi * d;
-            const uint32_t m = B.rowmask[qi];
-            if ((m >> qs) & 1u) {  // q is the node's first appearance
-              local = static_cast<uint32_t>(n) +
-                      static_cast<uint32_t>(B.tile_sums[qi / kTileRows] & 0xFFFFFFFFull) +
-                      static_cast<uint32_t>(B.newrank[qi]) + __popc(m & ((1u << qs) - 1u));
-              break;
-            }
-            const uint32_t nxt = B.ent[q] & ~kTagMask;  // strictly smaller position
-            if (nxt >= q) break;                        // cannot happen; guards the loop
-            q = nxt;
-          }
-        }
-        B.blk_indices[off_lds[r] + sl] = static_cast<int32_t>(local);
-      }
-    }
-  }
-}
-
-// Rows are moved as vectors of sizeof(V) bytes.  A block copies kGatherRows consecutive output
-// rows and exits: many short-lived blocks reach a higher copy rate on this chip than a persistent
-// grid-stride loop.  Inside a block the output chunk is addressed as one flat vector array, so
-// stores are fully coalesced and the lanes that share a row read one contiguous span of it.
-constexpr int kGatherRows = 32;
-template <typename V>
-__device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, int64_t row_stride,
-                                            uint32_t vec_per_row, const int32_t* __restrict__ ids,
-                                            int64_t n, uint8_t* __restrict__ out) {
-  constexpr int U = 2;
-  __shared__ int64_t row_byte[kGatherRows];  // byte offset of each source row
-  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
-  if (r0 >= n) return;
-  const uint32_t rows = static_cast<uint32_t>(n - r0 < kGatherRows ? n - r0 : kGatherRows);
-  const uint32_t cnt = rows * vec_per_row;
-  if (threadIdx.x < kGatherRows)
-    row_byte[threadIdx.x] = threadIdx.x < rows ? static_cast<int64_t>(ids[r0 + threadIdx.x]) * row_stride : 0;
-  __syncthreads();
-  V* __restrict__ o = reinterpret_cast<V*>(out) + static_cast<uint64_t>(r0) * vec_per_row;
-  uint32_t base = threadIdx.x;
-  // full rounds: U independent row reads in flight per thread, then the U stores
-  for (; base + (U - 1) * kThreads < cnt; base += kThreads * U) {
-    V val[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t idx = base + u * kThreads;
-      const uint32_t jrow = idx / vec_per_row;
-      const uint32_t c = idx - jrow * vec_per_row;
-      val[u] = __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(val[u], o + base + u * kThreads);
-  }
-  for (; base < cnt; base += kThreads) {
-    const uint32_t jrow = base / vec_per_row;
-    const uint32_t c = base - jrow * vec_per_row;
-    __builtin_nontemporal_store(
-        __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c), o + base);
-  }
-}
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-template <typename V>
-__global__ void __launch_bounds__(kThreads) k_gather(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  int64_t n = B.counts[P.L];
-  if (n > B.node_capacity) n = B.node_capacity;
-  gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), B.node_ids, n,
-                 B.features);
-}
-
-template <typename V>
-__global__ void __launch_bounds__(kThreads) k_gather_plain(const uint8_t* feat, int64_t row_bytes,
-                                                           int64_t row_stride, const int32_t* ids,
-                                                           const int64_t* num_rows, int64_t max_rows,
-                                                           uint8_t* out) {
-  int64_t n = *num_rows;
-  if (n > max_rows) n = max_rows;
-  if (n < 0) n = 0;
-  gather_rows<V>(feat, row_stride, static_cast<uint32_t>(row_bytes / sizeof(V)), ids, n, out);
-}
-
-// ---- wide path: fanouts above 32, or every neighbour (SMFG_FANOUT_ALL) ------------------------
-// Samples sit at their exact block offsets (pos = block indptr[i] + s), so a count + scan pass
-// comes first and the later passes walk the samples flat, four consecutive samples per thread.
-constexpr int kWideTile = 4 * kThreads;  // samples per flat tile
-
-// Degree, sample count and row start per destination; in-tile scan of the sample counts.
-__global__ void __launch_bounds__(kThreads) k_count_rows(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int d = P.d;
-  const int tiles = (n + kTileRows - 1) / kTileRows;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const int i = tile * kTileRows + threadIdx.x;
-    uint32_t k = 0;
-    if (i < n) {
-      const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
-      const int64_t a = P.indptr[v];
-      const uint32_t deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
-      k = (d < 0 || deg <= static_cast<uint32_t>(d)) ? deg : static_cast<uint32_t>(d);
-      B.rowstart[i] = a;
-      B.rowdeg[i] = deg;
-      B.rowk[i] = static_cast<int32_t>(k);
-    }
-    unsigned long long total;
-    const unsigned long long pre = block_exscan(k, lds, total);
-    if (i < n) B.rowoff[i] = static_cast<int32_t>(pre);
-    if (threadIdx.x == 0) B.tile_sums[tile] = total;
-    __syncthreads();
-  }
-}
-
-// Exclusive scan of the per-tile sample counts; E_h and its capacity checks.
-__global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int tiles = (n + kTileRows - 1) / kTileRows;
-  unsigned long long carry = 0;
-  for (int t0 = 0; t0 < tiles; t0 += kThreads) {
-    const int t = t0 + threadIdx.x;
-    const unsigned long long x = t < tiles ? B.tile_sums[t] : 0ull;
-    unsigned long long total;
-    const unsigned long long ex = block_exscan(x, lds, total);
-    if (t < tiles) B.tile_sums[t] = carry + ex;
-    carry += total;
-  }
-  if (threadIdx.x == 0) {
-    const bool fits = carry <= static_cast<unsigned long long>(B.edge_capacity) &&
-                      carry <= static_cast<unsigned long long>(B.lostto_entries);
-    B.counts[P.L + 1 + P.h] = static_cast<int64_t>(carry);
-    if (fits) B.blk_indptr[n] = static_cast<int32_t>(carry);
-    else set_status(B, P.L, SMFG_ST_EDGE_CAPACITY);
-  }
-}
-
-// One wave per destination; lane l of round r owns slot s = 64 r + l.
-__global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P) {
-  __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  uint32_t* picks = picks_lds[wave];
-  const int waves_total = gridDim.x * (kThreads / 64);
-  for (int i = blockIdx.x * (kThreads / 64) + wave; i < n; i += waves_total) {
-    const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
-    const int64_t a = B.rowstart[i];
-    const uint32_t deg = static_cast<uint32_t>(B.rowdeg[i]);
-    const uint32_t k = static_cast<uint32_t>(B.rowk[i]);
-    const uint32_t base = static_cast<uint32_t>(B.tile_sums[i / kTileRows]) + static_cast<uint32_t>(B.rowoff[i]);
-    if (lane == 0) B.blk_indptr[i] = static_cast<int32_t>(base);
-    const bool floyd = deg > k;  // only then are positions drawn (k = fanout <= SMFG_MAX_WIDE_FANOUT)
-    for (uint32_t s0 = 0; s0 < k; s0 += 64) {
-      const uint32_t s = s0 + static_cast<uint32_t>(lane);
-      const bool active = s < k;
-      uint32_t p = s;  // whole row in CSR order when nothing is drawn
-      if (floyd) {
-        uint32_t t = 0, j = 0;
-        if (active) {
-          const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), s >> 2, B.key0, B.key1, s & 3u);
-          j = deg - k + s;
-          t = __umulhi(w, j + 1u);  // index in [0, j]
-        }
-        // Floyd's rule slot by slot; the array set is picks[0, s0) in LDS plus the lanes of this round
-        const uint32_t round = k - s0 < 64u ? k - s0 : 64u;
-        for (uint32_t q = 0; q < round; ++q) {
-          const uint32_t tq = __shfl(t, static_cast<int>(q), 64);
-          bool hit = static_cast<uint32_t>(lane) < q && p == tq;
-          for (uint32_t l = static_cast<uint32_t>(lane); l < s0; l += 64) hit = hit || picks[l] == tq;
-          const bool any = __ballot(hit) != 0ull;
-          if (static_cast<uint32_t>(lane) == q) p = any ? j : tq;
-        }
-        if (active) picks[s] = p;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // later rounds read all lanes' picks
-        __builtin_amdgcn_wave_barrier();
-      }
-      if (active) {
-        const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
-        const uint32_t pos = base + s;
-        uint32_t slot;
-        bool full;
-        const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
-        if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
-        uint32_t e = prev;  // see k_sample_insert for the three cases
-        if (prev > (kPend | pos)) {
-          e = kSlot | slot;
-          if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
-        }
-        B.ent[pos] = e;
-        B.gsrc[pos] = static_cast<int32_t>(g);
-      }
-    }
-  }
-}
-
-// Flat over the samples: first appearances, their in-tile ranks, per-tile totals.
-__global__ void __launch_bounds__(kThreads) k_flag_flat(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) {
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < B.lostto_entries;
-         q += static_cast<int64_t>(gridDim.x) * kThreads)
-      B.lostto[q] = 0u;
-    return;
-  }
-  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
-  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
-    uint32_t first[4];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      first[u] = 0;
-      const uint32_t pos = p0 + u;
-      if (pos < E) {
-        const uint32_t lost = B.lostto[pos];
-        if (lost != 0u) {
-          B.ent[pos] = lost;
-          B.lostto[pos] = 0u;
-        } else {
-          first[u] = (B.ent[pos] & kTagMask) == kSlot ? 1u : 0u;
-        }
-      }
-      mine += first[u];
-    }
-    unsigned long long total;
-    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (p0 + u < E) B.rank[p0 + u] = pre;
-      pre += first[u];
-    }
-    if (threadIdx.x == 0) B.stile_sums[tile] = total;
-    __syncthreads();
-  }
-}
-
-// Exclusive scan of the per-tile counts of new nodes; n_{h+1} and its capacity check.
-__global__ void __launch_bounds__(kThreads) k_scan_flat_tiles(const Launch P) {
-  __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
-  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
-  unsigned long long carry = 0;
-  for (uint32_t t0 = 0; t0 < tiles; t0 += kThreads) {
-    const uint32_t t = t0 + threadIdx.x;
-    const unsigned long long x = t < tiles ? B.stile_sums[t] : 0ull;
-    unsigned long long total;
-    const unsigned long long ex = block_exscan(x, lds, total);
-    if (t < tiles) B.stile_sums[t] = carry + ex;
-    carry += total;
-  }
-  if (threadIdx.x == 0) {
-    const int64_t nodes = static_cast<int64_t>(n) + static_cast<int64_t>(carry);
-    B.counts[P.h + 1] = nodes;
-    if (nodes > B.node_capacity) set_status(B, P.L, SMFG_ST_NODE_CAPACITY);
-  }
-}
-
-// Flat over the samples: final local ids -> block indices; first appearances publish themselves.
-__global__ void __launch_bounds__(kThreads) k_assemble_flat(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
-  const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
-  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
-  const bool last = P.h == P.L - 1;
-  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-    const uint32_t tpre = n + static_cast<uint32_t>(B.stile_sums[tile]);
-    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint32_t pos = p0 + u;
-      if (pos >= E) continue;
-      const uint32_t e = B.ent[pos];
-      const uint32_t tag = e & kTagMask;
-      uint32_t local = e;
-      if (tag == kSlot) {
-        local = tpre + B.rank[pos];
-        const uint32_t g = static_cast<uint32_t>(B.gsrc[pos]);
-        B.node_ids[local] = static_cast<int32_t>(g);
-        if (!last) B.table[e & ~kTagMask] = (static_cast<uint64_t>(g) << 32) | local;
-      } else if (tag != 0u) {  // kPend: same node as the sample at position q < pos
-        uint32_t q = e & ~kTagMask;
-        for (;;) {
-          const uint32_t eq = B.ent[q];
-          if ((eq & kTagMask) == kSlot) {  // q is the node's first appearance
-            local = n + static_cast<uint32_t>(B.stile_sums[q / kWideTile]) + B.rank[q];
-            break;
-          }
-          const uint32_t nxt = eq & ~kTagMask;  // strictly smaller position
-          if (nxt >= q) break;                  // cannot happen; guards the loop
-          q = nxt;
-        }
-      }
-      B.blk_indices[pos] = static_cast<int32_t>(local);
-    }
-  }
-}
-
-// ---- a consumer: GraphSAGE mean aggregation over one block -------------------------------------
-// 16 lanes per destination; a lane owns V consecutive columns per round of 16 * V columns and
-// accumulates its destination's sampled source rows in float, slot order, two rows in flight.
-constexpr int kAggLanes = 16;
-constexpr int kAggRows = kThreads / kAggLanes;
-
-template <typename T, int V>
-struct alignas(sizeof(T) * V) RowVec {
-  T v[V];
-};
-
-__device__ __forceinline__ float to_float(_Float16 h) { return static_cast<float>(h); }
-__device__ __forceinline__ float to_float(float f) { return f; }
-
-template <typename T, int V>
-__global__ void __launch_bounds__(kThreads) k_mean_aggregate(const int32_t* __restrict__ indptr,
-                                                             const int32_t* __restrict__ indices,
-                                                             const int64_t* __restrict__ num_dst, int64_t max_dst,
-                                                             const T* __restrict__ x, int dim,
-                                                             float* __restrict__ out) {
-  int64_t n = *num_dst;
-  if (n > max_dst) n = max_dst;
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * kAggRows + threadIdx.x / kAggLanes;
-  if (i >= n) return;
-  const int lane = threadIdx.x & (kAggLanes - 1);
-  const int e0 = indptr[i], e1 = indptr[i + 1];
-  const float k = static_cast<float>(e1 - e0);
-  typedef RowVec<T, V> Vec;
-  for (int c = lane * V; c < dim; c += kAggLanes * V) {
-    float acc[V];
-#pragma unroll
-    for (int t = 0; t < V; ++t) acc[t] = 0.f;
-    int e = e0;
-    for (; e + 1 < e1; e += 2) {
-      const Vec a = *reinterpret_cast<const Vec*>(x + static_cast<int64_t>(indices[e]) * dim + c);
-      const Vec b = *reinterpret_cast<const Vec*>(x + static_cast<int64_t>(indices[e + 1]) * dim + c);
-#pragma unroll
-      for (int t = 0; t < V; ++t) acc[t] = (acc[t] + to_float(a.v[t])) + to_float(b.v[t]);
-    }
-    if (e < e1) {
-      const Vec a = *reinterpret_cast<const Vec*>(x + static_cast<int64_t>(indices[e]) * dim + c);
-#pragma unroll
-      for (int t = 0; t < V; ++t) acc[t] += to_float(a.v[t]);
-    }
-    float* o = out + i * dim + c;
-#pragma unroll
-    for (int t = 0; t < V; ++t) o[t] = e1 > e0 ? acc[t] / k : 0.f;
-  }
-}
+using namespace smfg_dev;
 
 // ---- host side --------------------------------------------------------------------------------
 
