@@ -152,19 +152,22 @@ def main():
         outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
     row_bytes = g.row_bytes
 
-    K = max(G, (args.steps // G) * G)
-    W = -(-args.warmup // G) * G if args.warmup > 0 else 0
+    K = max(1, args.steps)      # exactly K timed batches; the last launch set may be partial
+    W = max(0, args.warmup)
     keys = [synth.batch_rng_key(w, i) for i in range(len(batches))]
     counts_all = torch.zeros((K + W, 2 * L + 2), dtype=torch.int64, device=dev)
     stride = counts_all.stride(0) * 8
 
-    last_call = {}   # buffer set -> first batch index of the last launch set that used it
+    last_call = {}   # buffer set -> (first batch index, batches) of the last launch set that used it
+    sets_issued = [0]
 
     def run_pipelined(first, n):
         for c in range(first, first + n, G):
-            q = (c // G) % 2
-            last_call[q] = c
-            idx = [(c + b) % len(batches) for b in range(G)]
+            k = min(G, first + n - c)
+            q = sets_issued[0] % 2
+            sets_issued[0] += 1
+            last_call[q] = (c, k)
+            idx = [(c + b) % len(batches) for b in range(k)]
 
             def point_counts(os_, c=c):
                 for b, o in enumerate(os_):
@@ -175,17 +178,19 @@ def main():
         if args.pipeline:
             return run_pipelined(first, n)
         for c in range(first, first + n, G):
-            q = (c // G) % S
-            last_call[q] = c
-            idx = [(c + b) % len(batches) for b in range(G)]
-            for b in range(G):
+            k = min(G, first + n - c)
+            q = sets_issued[0] % S
+            sets_issued[0] += 1
+            last_call[q] = (c, k)
+            idx = [(c + b) % len(batches) for b in range(k)]
+            for b in range(k):
                 outs[q][b].c.counts = counts_all.data_ptr() + (c + b) * stride
-            smfg.sample_mfg_many(g, wss[q], [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx],
-                                 outs[q], stream=streams[q])
+            smfg.sample_mfg_many(g, wss[q][:k], [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx],
+                                 outs[q][:k], stream=streams[q])
 
     run_calls(0, W)
     torch.cuda.synchronize()
-    smfg.profile_begin(1, K // G)
+    smfg.profile_begin(1, K // G + 2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     run_calls(W, K)
@@ -206,12 +211,12 @@ def main():
     # launch sets are still in place): the kernel's own rate, next to the overlapped one above.
     smfg.profile_begin(1, 16)
     rows_alone = 0
-    timed_sets = [q for q, c in last_call.items() if c >= W]
+    timed_sets = [q for q, (c, k) in last_call.items() if c >= W]
     for rep in range(6):
         q = timed_sets[rep % len(timed_sets)]
-        smfg.gather_many(g, outs[q], stream=streams[0])
-        c0 = last_call[q] - W
-        rows_alone += sum(c[L] for c in cnt[c0:c0 + G])
+        c0, k = last_call[q][0] - W, last_call[q][1]
+        smfg.gather_many(g, outs[q][:k], stream=streams[0])
+        rows_alone += sum(c[L] for c in cnt[c0:c0 + k])
     torch.cuda.synchronize()
     alone_ms, alone_launches = smfg.profile_end()["gather"]
     alone_gbs = 2 * row_bytes * rows_alone / (alone_ms * 1e-3) / 1e9 if alone_ms > 0 else 0.0
@@ -220,13 +225,13 @@ def main():
     # over the outermost block of the batches of the last launch set.
     consumer = None
     if feat.dtype in (torch.float16, torch.float32):
-        q = timed_sets[0]
-        c0 = last_call[q] - W
+        q = max(timed_sets, key=lambda t: last_call[t][1])
+        c0, k_set = last_call[q][0] - W, last_call[q][1]
         agg_out = torch.empty((outs[q][0].node_capacity, w.feat_dim), dtype=torch.float32, device=dev)
         smfg.profile_begin(2, 4 * G)
         agg_bytes = 0
         for rep in range(2):
-            for b in range(G):
+            for b in range(k_set):
                 o, c = outs[q][b], cnt[c0 + b]
                 o.c.counts = counts_all.data_ptr() + (W + c0 + b) * stride
                 n_dst, e_last = c[L - 1], c[2 * L]
@@ -271,7 +276,7 @@ def main():
         result["consumer"] = consumer
 
     if args.stages:
-        smfg.profile_begin(2, 64 * (K // G))
+        smfg.profile_begin(2, 64 * (K // G + 2))
         run_calls(W, K)
         st = smfg.profile_end()
         result["stage_ms_per_batch"] = {s: ms / K for s, (ms, _) in st.items()}
