@@ -432,3 +432,51 @@ def test_launch_set_replays_from_a_hip_graph(tiny):
             src = (b + shift) % len(batches)
             ref = refs.setdefault((src, b), gg.oracle.sample_mfg(batches[src].numpy(), w.fanouts, keys[b]))
             assert_same(fetch(outs[b], L), ref, L)
+
+
+def test_one_bad_batch_does_not_disturb_the_others(tiny):
+    """In a launch set, a batch with a duplicate seed, one with an out-of-range seed and one whose
+    node capacity is too small end with their own status; the remaining batches match the oracle."""
+    w, gg, batches = tiny
+    fan = w.fanouts
+    good = [batches[0].numpy(), batches[1].numpy()]
+    dup = batches[2].numpy().copy(); dup[3] = dup[77]
+    oob = batches[3].numpy().copy(); oob[100] = -5
+    seeds = [good[0], dup, good[1], oob, batches[2].numpy()]
+    caps = [None, None, None, None, 1000]           # the last one overflows its node capacity
+    wss = [smfg.workspace_create(gg.g, 256, fan) for _ in seeds]
+    outs = [smfg.alloc_output(gg.g, 256, fan, node_capacity=c) for c in caps]
+    keys = [50 + i for i in range(len(seeds))]
+    for rep in range(2):
+        smfg.sample_mfg_many(gg.g, wss, [torch.from_numpy(x).to(DEV) for x in seeds], fan, keys, outs)
+        st = [fetch(o, 2) for o in outs]
+        assert st[1]["status"] == smfg.ST_DUPLICATE_SEED and st[3]["status"] == smfg.ST_SEED_OUT_OF_RANGE
+        assert st[4]["status"] == smfg.ST_NODE_CAPACITY
+        assert_same(st[0], gg.oracle.sample_mfg(seeds[0], fan, keys[0]), 2)
+        assert_same(st[2], gg.oracle.sample_mfg(seeds[2], fan, keys[2]), 2)
+
+
+def test_wide_path_overload_and_recovery():
+    """Wide path with a node capacity far too small: table full or node capacity status, then the
+    same workspace serves a call that fits."""
+    rng = np.random.default_rng(12)
+    adj = random_simple_graph(2000, 16, rng, hub=500)
+    indptr, indices = csr_from_adj(adj)
+    gg = GpuGraph(indptr, indices, None)
+    seeds = np.concatenate([[0], rng.choice(np.arange(1, 2000), size=99, replace=False)]).astype(np.int32)
+    m = len(indices)
+    ws = smfg.workspace_create(gg.g, 100, (-1, 40), node_capacity=150, sample_capacity=m)
+    out = smfg.alloc_output(gg.g, 100, (-1, 40), node_capacity=150, edge_capacity=[m, m])
+    for rep in range(2):
+        smfg.sample_mfg(gg.g, ws, torch.from_numpy(seeds).to(DEV), (-1, 40), 3, out)
+        assert fetch(out, 2)["status"] in (smfg.ST_TABLE_FULL, smfg.ST_NODE_CAPACITY)
+        few = seeds[1:4].copy()
+        smfg.sample_mfg(gg.g, ws, torch.from_numpy(few).to(DEV), (-1, 40), 4, out)
+        ref = gg.oracle.sample_mfg(few, (-1, 40), 4)
+        if ref.num_nodes[-1] <= 150:
+            assert_same(fetch(out, 2), ref, 2)
+        else:
+            assert fetch(out, 2)["status"] != 0
+        one = smfg.alloc_output(gg.g, 100, (40,), node_capacity=150, edge_capacity=[m])
+        smfg.sample_mfg(gg.g, ws, torch.from_numpy(few).to(DEV), (40,), 4, one)
+        assert_same(fetch(one, 1), gg.oracle.sample_mfg(few, (40,), 4), 1)
