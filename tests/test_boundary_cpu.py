@@ -43,3 +43,35 @@ def test_oracle_and_library_agree_on_bounds():
     for seeds, fan, n in [(256, (10, 5), 10_000), (4096, (20, 20, 20), 111_000_000), (5, (32,), 20),
                           (64, (100, 100), 5000), (8, (3, -1, 2), 900), (8, (-1,), 900)]:
         assert tuple(smfg.bounds(seeds, fan, n)) == tuple(oracle.worst_case(seeds, fan, n))
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/smfg.h compiles as C99 on its own (plain pointers and sizes, no C++ or torch types)
+    and every declared function can be referenced from C."""
+    import subprocess
+    names = [n for n in _declared()]
+    src = tmp_path / "use_header.c"
+    body = "\n".join(f"  p[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text('#include "smfg.h"\n#include <stddef.h>\n'
+                   f"void (*p[{len(names)}])(void);\n"
+                   "int use_all(void) {\n" + body + "\n  smfg_output_t o; o.node_capacity = 0;\n"
+                   "  return (int)sizeof(o) + SMFG_MAX_LAYERS + SMFG_FANOUT_ALL;\n}\n")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           "-c", str(src), "-o", str(tmp_path / "use_header.o")])
+
+
+def test_output_struct_layout_matches_the_binding(tmp_path):
+    """The ctypes mirror of smfg_output_t has the size and field offsets the C compiler gives."""
+    import subprocess
+    src = tmp_path / "layout.c"
+    fields = ["indptr", "indices", "node_ids", "features", "counts", "node_capacity", "edge_capacity", "labels"]
+    prints = "\n".join(f'  printf("{f} %zu\\n", offsetof(smfg_output_t, {f}));' for f in fields)
+    src.write_text('#include "smfg.h"\n#include <stddef.h>\n#include <stdio.h>\nint main(void) {\n'
+                   '  printf("size %zu\\n", sizeof(smfg_output_t));\n' + prints + "\n  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    got = dict(line.split() for line in subprocess.check_output([str(exe)], text=True).splitlines())
+    assert int(got["size"]) == ctypes.sizeof(smfg._Output)
+    for f in fields:
+        assert int(got[f]) == getattr(smfg._Output, f).offset, f
+    assert smfg.MAX_LAYERS == 8 and smfg.MAX_BATCHES == 16 and smfg.MAX_FANOUT == 32
