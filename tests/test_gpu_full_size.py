@@ -80,3 +80,81 @@ def test_papers_inference_shaped_batches(papers):
     w = synth.WORKLOADS["papers_infer"]
     batches = synth.make_seed_batches(w, device=DEV)
     _check_batches(w, graph, feat, g, orc, batches, [0, len(batches) - 1], 2)
+
+
+def _full_pass(w, graph, feat, g, base_oracle, threads=12, per_call=8):
+    """Every batch of one pass over the seed split: GPU in launch sets of `per_call`, the oracle on
+    host threads (one scratch map each); counts, node ids and blocks compared bit for bit, feature
+    rows against torch indexing."""
+    from concurrent.futures import ThreadPoolExecutor
+    import queue
+    L = len(w.fanouts)
+    batches = synth.make_seed_batches(w, device=DEV)
+    h_batches = [b.cpu().numpy() for b in batches]
+    keys = [synth.batch_rng_key(w, b) for b in range(len(batches))]
+    pool_oracles = queue.Queue()
+    pool_oracles.put(base_oracle)
+    for _ in range(threads - 1):
+        pool_oracles.put(base_oracle.clone_scratch())
+
+    def ref_of(b):
+        o = pool_oracles.get()
+        try:
+            return o.sample_mfg(h_batches[b], w.fanouts, keys[b], with_features=False)
+        finally:
+            pool_oracles.put(o)
+
+    wss = [smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(per_call)]
+    outs = [smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(per_call)]
+    total_nodes = total_edges = 0
+    with ThreadPoolExecutor(threads) as ex:
+        for c0 in range(0, len(batches), per_call):
+            ids = list(range(c0, min(len(batches), c0 + per_call)))
+            refs = [ex.submit(ref_of, b) for b in ids]
+            k = len(ids)
+            smfg.sample_mfg_many(g, wss[:k], [batches[b] for b in ids], w.fanouts, [keys[b] for b in ids], outs[:k])
+            for q, b in enumerate(ids):
+                ref = refs[q].result()
+                c = smfg.read_counts(outs[q])
+                assert ref.status == 0 and c == [int(x) for x in ref.counts], f"batch {b}"
+                n, e = c[:L + 1], c[L + 1:2 * L + 1]
+                assert np.array_equal(outs[q].node_ids[:n[L]].cpu().numpy(), ref.node_ids), f"batch {b}"
+                for h in range(L):
+                    assert np.array_equal(outs[q].indptr[h][:n[h] + 1].cpu().numpy(), ref.indptr[h]), (b, h)
+                    assert np.array_equal(outs[q].indices[h][:e[h]].cpu().numpy(), ref.indices[h]), (b, h)
+                assert torch.equal(outs[q].features[:n[L]], feat[outs[q].node_ids[:n[L]].long()]), f"batch {b}"
+                total_nodes += n[L]
+                total_edges += sum(e)
+            if c0 % (per_call * 16) == 0:
+                print(f"{w.name}: {c0 + k} of {len(batches)} batches identical", flush=True)
+    print(f"{w.name}: full pass of {len(batches)} batches identical, {total_nodes} nodes, {total_edges} edges",
+          flush=True)
+
+
+def test_mid_workload_full_pass():
+    w = synth.WORKLOADS["mid"]
+    graph = synth.make_graph(w, device=DEV)
+    feat = synth.make_features(w, device=DEV)
+    g = smfg.graph_create(graph.indptr, graph.indices, feat)
+    _full_pass(w, graph, feat, g, oracle.Oracle(graph.indptr.cpu().numpy(), graph.indices.cpu().numpy()))
+
+
+def test_large_workload_full_pass():
+    w = synth.WORKLOADS["large"]
+    graph = synth.make_graph(w, device=DEV)
+    feat = synth.make_features(w, device=DEV)
+    g = smfg.graph_create(graph.indptr, graph.indices, feat)
+    _full_pass(w, graph, feat, g, oracle.Oracle(graph.indptr.cpu().numpy(), graph.indices.cpu().numpy()))
+
+
+def test_papers_workload_full_pass(papers):
+    """All 1193 batches of the pass over the 1.1 % train split of the papers100M-shaped graph."""
+    graph, feat, g, orc = papers
+    _full_pass(synth.WORKLOADS["papers"], graph, feat, g, orc)
+
+
+def test_papers_inference_full_pass(papers):
+    """All 55 batches of the held-out split with fanouts (20,20,20): about 1.07 G nodes and 1.4 G
+    edges in total."""
+    graph, feat, g, orc = papers
+    _full_pass(synth.WORKLOADS["papers_infer"], graph, feat, g, orc, threads=8, per_call=2)
