@@ -404,9 +404,13 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     }
     if (o.node_capacity < 1) return SMFG_ERR_INVALID_ARG;
     if (num_seeds[b] > w->max_seeds || num_seeds[b] > o.node_capacity) return SMFG_ERR_TOO_MANY_SEEDS;
-    if (o.node_capacity > w->node_capacity) return SMFG_ERR_CAPACITY;
+    // the nodes this call can reach at most; a roomier output buffer does not ask more of the workspace
+    int64_t bn[SMFG_MAX_LAYERS + 1], be[SMFG_MAX_LAYERS];
+    smfg_bounds(num_seeds[b], L, fanouts, g->num_nodes, bn, be);
+    const int64_t ncap = o.node_capacity < bn[L] ? o.node_capacity : (bn[L] > 0 ? bn[L] : 1);
+    if (ncap > w->node_capacity) return SMFG_ERR_CAPACITY;
     // fast path: padded positions must fit; wide path: E_h is checked on the device
-    if (!wide && slot_entries_needed(num_seeds[b], L, fanouts, g->num_nodes, o.node_capacity) > w->slot_entries)
+    if (!wide && slot_entries_needed(num_seeds[b], L, fanouts, g->num_nodes, ncap) > w->slot_entries)
       return SMFG_ERR_CAPACITY;
     if (w->slot_entries > max_entries) max_entries = w->slot_entries;
     if (g->feat && o.features) {
@@ -444,7 +448,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
         return SMFG_ERR_INVALID_ARG;
     }
     B.labels = static_cast<uint8_t*>(o.labels);
-    B.node_capacity = static_cast<int32_t>(o.node_capacity);
+    B.node_capacity = static_cast<int32_t>(ncap);
     B.num_seeds = num_seeds[b];
     B.key0 = static_cast<uint32_t>(rng_keys[b]);
     B.key1 = static_cast<uint32_t>(rng_keys[b] >> 32);
@@ -455,7 +459,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
 
     int64_t n = num_seeds[b] < g->num_nodes ? num_seeds[b] : g->num_nodes;
     for (int h = 0; h <= L; ++h) {
-      if (n > o.node_capacity) n = o.node_capacity;
+      if (n > ncap) n = ncap;
       if (n > max_n[h]) max_n[h] = n;
       if (h < L) {
         n = fanouts[h] < 0 ? g->num_nodes : n + n * fanouts[h];

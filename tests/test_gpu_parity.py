@@ -480,3 +480,63 @@ def test_wide_path_overload_and_recovery():
         one = smfg.alloc_output(gg.g, 100, (40,), node_capacity=150, edge_capacity=[m])
         smfg.sample_mfg(gg.g, ws, torch.from_numpy(few).to(DEV), (40,), 4, one)
         assert_same(fetch(one, 1), gg.oracle.sample_mfg(few, (40,), 4), 1)
+
+
+def test_multigraph_rows_and_self_loops():
+    """Rows with repeated neighbours and self loops: sampling is over row positions, so a block row
+    may name the same source twice and a node may be its own neighbour; the oracle defines it."""
+    rng = np.random.default_rng(77)
+    n = 500
+    adj = []
+    for v in range(n):
+        k = int(rng.integers(0, 30))
+        row = rng.integers(0, n, size=k).tolist()          # with repeats
+        if v % 7 == 0:
+            row += [v, v]                                   # self loops, twice
+        adj.append(row)
+    indptr, indices = csr_from_adj(adj)
+    gg = GpuGraph(indptr, indices, rng.standard_normal((n, 4)).astype(np.float32))
+    seeds = rng.choice(n, size=64, replace=False).astype(np.int32)
+    for fan in [(5, 5), (32,), (3, 3, 3), (-1, 4), (40, -1)]:
+        ref = gg.oracle.sample_mfg(seeds, fan, 9)
+        m = len(indices)
+        ws = smfg.workspace_create(gg.g, 64, fan, node_capacity=n, sample_capacity=m)
+        out = smfg.alloc_output(gg.g, 64, fan, node_capacity=n, edge_capacity=[m] * len(fan))
+        smfg.sample_mfg(gg.g, ws, torch.from_numpy(seeds).to(DEV), fan, 9, out)
+        assert_same(fetch(out, len(fan)), ref, len(fan))
+
+
+def test_giant_hub_and_isolated_seeds():
+    """A hub of degree 120 000 (more than 2^16 positions to draw from, many Floyd rounds on the wide
+    path, a row of 1875 rounds when every neighbour is taken) and a batch of isolated seeds."""
+    rng = np.random.default_rng(5)
+    n = 150_000
+    hub_nbrs = np.sort(rng.choice(np.arange(1, n), size=120_000, replace=False))
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    deg = np.zeros(n, dtype=np.int64)
+    deg[0] = len(hub_nbrs)
+    deg[hub_nbrs] = 1
+    indptr[1:] = np.cumsum(deg)
+    indices = np.zeros(int(indptr[-1]), dtype=np.int32)
+    indices[:len(hub_nbrs)] = hub_nbrs                      # row 0; every neighbour's row is [0]
+    gg = GpuGraph(indptr, indices, None)
+    lonely = np.setdiff1d(np.arange(1, n), hub_nbrs)[:50].astype(np.int32)
+    seeds = np.concatenate([[0], hub_nbrs[:20]]).astype(np.int32)
+    m = len(indices)
+    for fan in [(32, 2), (10,), (1024,), (-1,), (-1, 3), (500, -1)]:
+        for s in (seeds, lonely):
+            ref = gg.oracle.sample_mfg(s, fan, 1234)
+            ws = smfg.workspace_create(gg.g, len(s), fan, node_capacity=n, sample_capacity=m)
+            out = smfg.alloc_output(gg.g, len(s), fan, node_capacity=n, edge_capacity=[m] * len(fan))
+            smfg.sample_mfg(gg.g, ws, torch.from_numpy(s).to(DEV), fan, 1234, out)
+            assert_same(fetch(out, len(fan)), ref, len(fan))
+    assert gg.oracle.sample_mfg(lonely, (5, 5), 1).num_edges == [0, 0]
+
+
+def test_single_node_graph():
+    indptr = np.array([0, 0], dtype=np.int64)
+    indices = np.zeros(0, dtype=np.int32)
+    gg = GpuGraph(indptr, indices, np.ones((1, 2), dtype=np.float32))
+    res = run_one(gg, np.array([0], dtype=np.int32), (4, 4), 3)
+    assert_same(res, gg.oracle.sample_mfg(np.array([0], dtype=np.int32), (4, 4), 3), 2)
+    assert res["counts"] == [1, 1, 1, 0, 0, 0]
