@@ -111,7 +111,8 @@ int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t *fanouts, int64_t nu
  * Scratch for one batch in flight: dedup table (>= 2 slots per node of capacity), per-sample
  * slot memory, per-row counters, scan partials.  Sized for up to max_seeds seeds, the given
  * fanouts (a later call may use the same or smaller fanouts / fewer hops) and node_capacity
- * distinct nodes (0 = the worst case of smfg_bounds).  Allocates device memory with hipMalloc.
+ * distinct nodes (0 = the worst case of smfg_bounds).  Allocates device memory with hipMalloc,
+ * zeroes part of it and synchronises the device once; not for use inside a stream capture.
  */
 int smfg_workspace_create(smfg_workspace_t **out, const smfg_graph_t *g, int32_t max_seeds,
                           int32_t L, const int32_t *fanouts, int64_t node_capacity);
