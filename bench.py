@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--stages", action="store_true", help="extra untimed pass with every launch timed")
+    ap.add_argument("--consume", action="store_true",
+                    help="extra untimed-for-value pass: a consumer stream runs the mean aggregation of all hops "
+                         "on every prepared batch while the next launch set is being prepared")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run plain copies of known size (1 GiB in, 1 GiB out) for counter calibration")
     args = ap.parse_args()
@@ -274,6 +277,50 @@ def main():
 
     if consumer is not None:
         result["consumer"] = consumer
+
+    if args.consume and pipe is not None and feat.dtype in (torch.float16, torch.float32):
+        # Preparation hidden behind a consumer (the paper's pipelining, section 4.3, with everything on
+        # one GPU): the consumer aggregates hop L-1 .. 0 of each batch on the current stream.
+        n_b = min(K, 1024)
+        idx = [i % len(batches) for i in range(n_b)]
+        cap = pipe.outs[0][0].node_capacity
+        bufs = [torch.empty((cap, w.feat_dim), dtype=torch.float32, device=dev) for _ in range(2)]
+
+        def consume(o):
+            x = o.features
+            for h in range(L - 1, -1, -1):
+                y = bufs[h % 2]
+                smfg.mean_aggregate(o.indptr[h], o.indices[h], o.counts[h:h + 1], cap, x, y)
+                x = y
+
+        def one_pass(with_consumer):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for outs_ in pipe.run([batches[i] for i in idx], [keys[i] for i in idx]):
+                if with_consumer:
+                    for o in outs_:
+                        consume(o)
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0
+        for o_set in pipe.outs:           # each output needs its own counts buffer again
+            for o in o_set:
+                o.c.counts = o.counts.data_ptr()
+        one_pass(True)
+        t_prep = one_pass(False)
+        t_both = one_pass(True)
+        # the consumer alone, on the batches of the last set left in the buffers
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 8
+        for _ in range(reps):
+            for o in pipe.outs[0]:
+                consume(o)
+        torch.cuda.synchronize()
+        t_cons = (time.perf_counter() - t0) / (reps * len(pipe.outs[0]))
+        result["with_consumer"] = {"batches": n_b, "prepare_only_ms_per_batch": t_prep / n_b * 1e3,
+                                   "consumer_only_ms_per_batch": t_cons * 1e3,
+                                   "prepare_and_consume_ms_per_batch": t_both / n_b * 1e3,
+                                   "consumer": "mean aggregation of hops L-1..0 (fp32 out)"}
 
     if args.stages:
         smfg.profile_begin(2, 64 * (K // G + 2))
