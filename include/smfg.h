@@ -121,6 +121,9 @@ int smfg_workspace_create(smfg_workspace_t **out, const smfg_graph_t *g, int32_t
  * 0 = derive it from the fanouts as smfg_workspace_create does).  Needed when a fanout is
  * SMFG_FANOUT_ALL, or when the derived worst case (destinations x fanout) would exceed the 2^30
  * positions a hop can address.  A hop that draws more samples ends with SMFG_ST_EDGE_CAPACITY.
+ * Calls whose fanouts are all <= SMFG_MAX_FANOUT address samples at padded positions
+ * (destination x fanout + slot): for them the capacity must cover destinations x fanout of every
+ * hop, else the call returns SMFG_ERR_CAPACITY.
  */
 int smfg_workspace_create_sized(smfg_workspace_t **out, const smfg_graph_t *g, int32_t max_seeds,
                                 int32_t L, const int32_t *fanouts, int64_t node_capacity,

@@ -540,3 +540,34 @@ def test_single_node_graph():
     res = run_one(gg, np.array([0], dtype=np.int32), (4, 4), 3)
     assert_same(res, gg.oracle.sample_mfg(np.array([0], dtype=np.int32), (4, 4), 3), 2)
     assert res["counts"] == [1, 1, 1, 0, 0, 0]
+
+
+def test_randomised_small_dense_graphs():
+    """Many small dense graphs (few nodes, long rows, fanouts near the node count): almost every
+    sample is a duplicate of another, so ownership changes hands repeatedly and pointer chains
+    form; both paths, up to 16 batches per launch set, compared with the oracle."""
+    rng = np.random.default_rng(2024)
+    fan_choices = [(3,), (8, 8), (15, 10, 5), (32, 32), (5, 5, 5, 5), (31, 2), (40, 3), (7, 64), (-1, 6), (100, 100),
+                   (12, -1, 4)]
+    cases = 0
+    for trial in range(36):
+        n = int(rng.integers(20, 260))
+        avg = int(rng.integers(8, 70))
+        adj = random_simple_graph(n, min(avg, n - 1), rng, hub=int(rng.integers(1, n - 1)) if trial % 3 == 0 else None)
+        indptr, indices = csr_from_adj(adj)
+        m = max(1, len(indices))
+        gg = GpuGraph(indptr, indices, rng.standard_normal((n, 3)).astype(np.float32))
+        fan = fan_choices[trial % len(fan_choices)]
+        G = int(rng.integers(1, 17))
+        seeds = [rng.choice(n, size=int(rng.integers(1, min(n, 60))), replace=False).astype(np.int32) for _ in range(G)]
+        keys = [int(rng.integers(0, 2**62)) for _ in range(G)]
+        wide = any(d < 0 or d > 32 for d in fan)     # the padded fast path sizes its own scratch
+        wss = [smfg.workspace_create(gg.g, 64, fan, node_capacity=n, sample_capacity=m if wide else 0)
+               for _ in range(G)]
+        outs = [smfg.alloc_output(gg.g, 64, fan, node_capacity=n, edge_capacity=[m] * len(fan)) for _ in range(G)]
+        for rep in range(2):
+            smfg.sample_mfg_many(gg.g, wss, [torch.from_numpy(s).to(DEV) for s in seeds], fan, keys, outs)
+            for b in range(G):
+                assert_same(fetch(outs[b], len(fan)), gg.oracle.sample_mfg(seeds[b], fan, keys[b]), len(fan))
+                cases += 1
+    assert cases > 300
