@@ -87,6 +87,7 @@ def cpu_baseline(w, graph, feat, batches, keys, budget_s, threads, gpu_check):
         "sample": f"{n_total} batches of workload '{w.name}' ({per_thread} per thread, {threads} threads, "
                   f"one batch on one thread: {t_one * 1e3:.1f} ms)",
         "sampled_edges_per_s": sum(edges) / dt, "parity_vs_gpu": parity,
+        "one_thread_batches_per_s": 1.0 / t_one,
     }
 
 
