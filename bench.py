@@ -63,7 +63,11 @@ def cpu_baseline(w, graph, feat, batches, keys, budget_s, threads, gpu_check):
     t0 = time.time()
     ref0 = base.sample_mfg(h_batches[0], w.fanouts, keys[0])
     t_one = time.time() - t0
+    # bit-for-bit comparison of the first batches with the GPU (bounded to a few seconds of oracle time)
+    n_check = max(1, min(8, len(h_batches), int(4.0 / max(t_one, 1e-3))))
     parity = gpu_check(ref0, 0)
+    for i in range(1, n_check):
+        parity = parity and gpu_check(base.sample_mfg(h_batches[i], w.fanouts, keys[i]), i)
     per_thread = max(1, min(int(budget_s / max(t_one, 1e-4)), 4096))
     n_total = per_thread * threads
     workers = [base] + [base.clone_scratch() for _ in range(threads - 1)]
@@ -86,7 +90,7 @@ def cpu_baseline(w, graph, feat, batches, keys, budget_s, threads, gpu_check):
         "value": n_total / dt, "unit": "batches/s", "cores": threads, "kind": "oracle",
         "sample": f"{n_total} batches of workload '{w.name}' ({per_thread} per thread, {threads} threads, "
                   f"one batch on one thread: {t_one * 1e3:.1f} ms)",
-        "sampled_edges_per_s": sum(edges) / dt, "parity_vs_gpu": parity,
+        "sampled_edges_per_s": sum(edges) / dt, "parity_vs_gpu": parity, "parity_batches": n_check,
         "one_thread_batches_per_s": 1.0 / t_one,
     }
 
