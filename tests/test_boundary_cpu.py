@@ -75,3 +75,10 @@ def test_output_struct_layout_matches_the_binding(tmp_path):
     for f in fields:
         assert int(got[f]) == getattr(smfg._Output, f).offset, f
     assert smfg.MAX_LAYERS == 8 and smfg.MAX_BATCHES == 16 and smfg.MAX_FANOUT == 32
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
