@@ -28,9 +28,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 # HBM bytes per k_gather launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (profiles/papers_kernel_trace_and_hbm_traffic.txt), scaled by what the same counters read
+# command (profiles/*_kernel_trace_and_hbm_traffic.txt), scaled by what the same counters read
 # for the identity copy of known size; keyed by (workload, batches per launch).
-MEASURED_GATHER_TRAFFIC_BYTES = {("papers", 8): 3.610e9}
+MEASURED_GATHER_TRAFFIC_BYTES = {("papers", 8): 3.610e9, ("large", 8): 2.414e9}
 
 
 def log(*a):
@@ -108,6 +108,8 @@ def main():
                     help="1: gather of launch set i runs on a second stream while set i+1 is sampled (two "
                          "buffer sets); 0: every launch set runs start to end on one stream (see --streams)")
     ap.add_argument("--feat-dim", type=int, default=0, help="experiment: override the feature width")
+    ap.add_argument("--row-stride", type=int, default=0,
+                    help="experiment: feature row stride in bytes (>= row bytes; 0 = dense rows)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
     ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
     ap.add_argument("--no-cpu", action="store_true")
@@ -138,6 +140,13 @@ def main():
     log(f"[gen] graph '{w.name}': {graph.num_nodes} nodes, {graph.num_edges} directed edges, {time.time() - t0:.1f}s")
     t0 = time.time()
     feat = synth.make_features(w, device=dev)
+    if args.row_stride:
+        eb = feat.element_size()
+        assert args.row_stride % eb == 0 and args.row_stride >= feat.shape[1] * eb
+        padded = torch.zeros((feat.shape[0], args.row_stride // eb), dtype=feat.dtype, device=dev)
+        padded[:, :feat.shape[1]] = feat
+        feat = padded[:, :feat.shape[1]]      # same values, rows args.row_stride bytes apart
+        del padded
     batches = synth.make_seed_batches(w, device=dev)
     torch.cuda.synchronize()
     log(f"[gen] features {tuple(feat.shape)} {feat.dtype}, {len(batches)} seed batches, {time.time() - t0:.1f}s")
@@ -263,6 +272,7 @@ def main():
         "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {graph.num_edges} directed edges, "
                                f"features {w.feat_dim}x{str(w.feat_dtype).split('.')[-1]}, fanouts {list(w.fanouts)}, "
                                f"batch {w.batch_size}", "batches_per_call": G, "streams": S, "pipeline": bool(args.pipeline),
+                   "row_stride_bytes": int(feat.stride(0) * feat.element_size()),
                    "mean_nodes_per_batch": n_final / K, "mean_edges_per_batch": edges / K},
         "sampled_edges_per_s": edges / dt,
         "gather_GBps": gather_gbs,
@@ -270,7 +280,7 @@ def main():
         "path_frac_of_hbm_peak": alg / dt / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
-                     "traffic": MEASURED_GATHER_TRAFFIC_BYTES.get((w.name, G)), "traffic_unit": "bytes per launch",
+                     "traffic": None if (args.feat_dim or args.row_stride) else MEASURED_GATHER_TRAFFIC_BYTES.get((w.name, G)), "traffic_unit": "bytes per launch",
                      "avg_launch_ms": gather_ms / max(1, gather_launches),
                      "note": "achieved is measured inside the timed region, where (with --pipeline 1) the gather "
                              "shares the chip with the sampling kernels of the next launch set; alone_* is the same "
@@ -338,7 +348,7 @@ def main():
         b = torch.empty_like(a)
         torch.cuda.synchronize()
         b.copy_(a)                       # plain device copy: 1 GiB read, 1 GiB written
-        rows = (1 << 30) // row_bytes
+        rows = min((1 << 30) // row_bytes, graph.num_nodes)   # identity ids must stay inside the feature table
         ids = torch.arange(rows, dtype=torch.int32, device=dev)
         nrows = torch.tensor([rows], dtype=torch.int64, device=dev)
         dst = b.view(torch.uint8)[:rows * row_bytes].view(feat.dtype).view(rows, -1)

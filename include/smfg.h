@@ -60,6 +60,7 @@ extern "C" {
 #define SMFG_ERR_TOO_MANY_SEEDS (-5)  /* more seeds than the workspace / output was sized for */
 #define SMFG_ERR_OOM (-6)             /* scratch allocation failed */
 #define SMFG_ERR_CAPACITY (-7)        /* output capacities exceed what the workspace supports */
+#define SMFG_ERR_BAD_GRAPH (-8)       /* smfg_graph_validate found a broken CSR array */
 #define SMFG_ERR_HIP_BASE (-1000)     /* a HIP call failed: code = SMFG_ERR_HIP_BASE - hipError_t */
 
 /* device-detected conditions (value of counts[2L+1]) */
@@ -88,6 +89,21 @@ int smfg_graph_create(smfg_graph_t **out, int64_t num_nodes, int64_t num_edges,
                       const int64_t *d_indptr, const int32_t *d_indices, const void *d_feat,
                       int32_t feat_dim, int32_t elem_bytes, int64_t row_stride_bytes);
 int smfg_graph_destroy(smfg_graph_t *g);
+
+/*
+ * Optional check of the borrowed CSR arrays against the conditions above, for callers that do
+ * not trust their input: the sampling calls themselves check seeds, not the graph, and follow a
+ * bad offset or neighbour id out of bounds.  One streaming pass over d_indptr and d_indices on
+ * hip_stream, then a synchronisation of that stream; allocates and frees 4 bytes of device memory
+ * (not for use inside a stream capture).  Returns SMFG_OK, or SMFG_ERR_BAD_GRAPH with the OR of
+ * the SMFG_BAD_* bits below in *h_flags (host, may be NULL).  Duplicates inside a row are not
+ * looked for.
+ */
+#define SMFG_BAD_INDPTR_START 1u /* d_indptr[0] != 0 */
+#define SMFG_BAD_INDPTR_ORDER 2u /* some d_indptr[v+1] < d_indptr[v], or a degree >= 2^31 */
+#define SMFG_BAD_INDPTR_END 4u   /* d_indptr[num_nodes] != num_edges */
+#define SMFG_BAD_INDEX_RANGE 8u  /* some d_indices[e] outside [0, num_nodes) */
+int smfg_graph_validate(const smfg_graph_t *g, uint32_t *h_flags, void *hip_stream);
 
 /*
  * Optional label vector y (Listing 1: ys = y[ids[:batch_size]], the labels of the seed nodes).
@@ -170,6 +186,7 @@ int smfg_sample_mfg_many(const smfg_graph_t *g, smfg_workspace_t *const *ws,
 /*
  * Only the gather xs = x[ids] (Listing 1): out rows j < *d_num_rows (a device int64) are copied
  * from the graph's feature rows d_node_ids[j].  max_rows bounds the launch.  Asynchronous.
+ * An id outside [0, num_nodes) yields a copy of row 0: never a read outside the feature matrix.
  */
 int smfg_gather_rows(const smfg_graph_t *g, const int32_t *d_node_ids, const int64_t *d_num_rows,
                      int64_t max_rows, void *d_out, void *hip_stream);
@@ -178,8 +195,8 @@ int smfg_gather_rows(const smfg_graph_t *g, const int32_t *d_node_ids, const int
  * The gather stage of smfg_sample_mfg_many on its own, for callers that run it on another stream
  * than the sampling stages (a call with outs[b].features == NULL skips the gather; this function
  * does it later): for every batch b, rows j < counts[L] of outs[b].features are copied from the
- * feature rows outs[b].node_ids[j]; a batch whose status word is non-zero is skipped.  One launch
- * for all batches.  The caller orders it after the sampling call (same stream, or an event).
+ * feature rows outs[b].node_ids[j] (an id outside [0, num_nodes) reads row 0); a batch whose
+ * status word is non-zero is skipped.  One launch for all batches.  The caller orders it after the sampling call (same stream, or an event).
  */
 int smfg_gather_many(const smfg_graph_t *g, const smfg_output_t *outs, int32_t num_batches,
                      int32_t L, void *hip_stream);

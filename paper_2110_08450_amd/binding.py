@@ -22,14 +22,14 @@ MAX_BATCHES = 16
 
 OK = 0
 ERR_INVALID_ARG, ERR_NULL_PTR, ERR_BAD_FANOUT, ERR_TOO_MANY_LAYERS = -1, -2, -3, -4
-ERR_TOO_MANY_SEEDS, ERR_OOM, ERR_CAPACITY, ERR_HIP_BASE = -5, -6, -7, -1000
+ERR_TOO_MANY_SEEDS, ERR_OOM, ERR_CAPACITY, ERR_BAD_GRAPH, ERR_HIP_BASE = -5, -6, -7, -8, -1000
 ST_NODE_CAPACITY, ST_EDGE_CAPACITY, ST_TABLE_FULL, ST_SEED_OUT_OF_RANGE, ST_DUPLICATE_SEED = 1, 2, 3, 4, 5
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsmfg.so")
 
 EXPORTS = [
-    "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_set_labels", "smfg_bounds", "smfg_workspace_create",
-    "smfg_workspace_create_sized",
+    "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_validate", "smfg_graph_set_labels", "smfg_bounds",
+    "smfg_workspace_create", "smfg_workspace_create_sized",
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
     "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
         pp = ctypes.POINTER(ctypes.c_void_p)
         L.smfg_graph_create.argtypes = [pp, i64, i64, vp, vp, vp, i32, i32, i64]
         L.smfg_graph_destroy.argtypes = [vp]
+        L.smfg_graph_validate.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), vp]
         L.smfg_graph_set_labels.argtypes = [vp, vp, i32]
         L.smfg_bounds.argtypes = [i32, i32, ctypes.POINTER(i32), i64, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.smfg_workspace_create.argtypes = [pp, vp, i32, i32, ctypes.POINTER(i32), i64]
@@ -147,6 +148,18 @@ def graph_create(indptr: torch.Tensor, indices: torch.Tensor, feat: Optional[tor
                                  fd, eb, stride)
     _check(rc, "smfg_graph_create")
     return Graph(h, indptr, indices, feat)
+
+
+BAD_INDPTR_START, BAD_INDPTR_ORDER, BAD_INDPTR_END, BAD_INDEX_RANGE = 1, 2, 4, 8
+
+
+def graph_validate(g: Graph, stream: Optional[torch.cuda.Stream] = None) -> int:
+    """0 if the CSR arrays are consistent, else the OR of the BAD_* bits.  Synchronises the stream."""
+    flags = ctypes.c_uint32(0)
+    rc = lib().smfg_graph_validate(g.handle, ctypes.byref(flags), _stream_ptr(stream))
+    if rc != OK and rc != ERR_BAD_GRAPH:
+        _check(rc, "smfg_graph_validate")
+    return int(flags.value)
 
 
 def graph_set_labels(g: Graph, labels: Optional[torch.Tensor]) -> None:

@@ -10,19 +10,24 @@ namespace smfg_dev {
 // rows and exits: many short-lived blocks reach a higher copy rate on this chip than a persistent
 // grid-stride loop.  Inside a block the output chunk is addressed as one flat vector array, so
 // stores are fully coalesced and the lanes that share a row read one contiguous span of it.
+// A row id outside [0, num_nodes) is read as row 0, so that no id can cause a read outside x.
 constexpr int kGatherRows = 32;
 template <typename V>
 __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, int64_t row_stride,
-                                            uint32_t vec_per_row, const int32_t* __restrict__ ids,
-                                            int64_t n, uint8_t* __restrict__ out) {
+                                            uint32_t vec_per_row, int64_t num_nodes,
+                                            const int32_t* __restrict__ ids, int64_t n,
+                                            uint8_t* __restrict__ out) {
   constexpr int U = 2;
   __shared__ int64_t row_byte[kGatherRows];  // byte offset of each source row
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
   if (r0 >= n) return;
   const uint32_t rows = static_cast<uint32_t>(n - r0 < kGatherRows ? n - r0 : kGatherRows);
   const uint32_t cnt = rows * vec_per_row;
-  if (threadIdx.x < kGatherRows)
-    row_byte[threadIdx.x] = threadIdx.x < rows ? static_cast<int64_t>(ids[r0 + threadIdx.x]) * row_stride : 0;
+  if (threadIdx.x < kGatherRows) {
+    int64_t id = threadIdx.x < rows ? ids[r0 + threadIdx.x] : 0;
+    if (id < 0 || id >= num_nodes) id = 0;
+    row_byte[threadIdx.x] = id * row_stride;
+  }
   __syncthreads();
   V* __restrict__ o = reinterpret_cast<V*>(out) + static_cast<uint64_t>(r0) * vec_per_row;
   uint32_t base = threadIdx.x;
@@ -56,19 +61,19 @@ __global__ void __launch_bounds__(kThreads) k_gather(const Launch P) {
   if (status_of(B, P.L) != 0) return;
   int64_t n = B.counts[P.L];
   if (n > B.node_capacity) n = B.node_capacity;
-  gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), B.node_ids, n,
-                 B.features);
+  gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), P.num_nodes,
+                 B.node_ids, n, B.features);
 }
 
 template <typename V>
 __global__ void __launch_bounds__(kThreads) k_gather_plain(const uint8_t* feat, int64_t row_bytes,
-                                                           int64_t row_stride, const int32_t* ids,
-                                                           const int64_t* num_rows, int64_t max_rows,
-                                                           uint8_t* out) {
+                                                           int64_t row_stride, int64_t num_nodes,
+                                                           const int32_t* ids, const int64_t* num_rows,
+                                                           int64_t max_rows, uint8_t* out) {
   int64_t n = *num_rows;
   if (n > max_rows) n = max_rows;
   if (n < 0) n = 0;
-  gather_rows<V>(feat, row_stride, static_cast<uint32_t>(row_bytes / sizeof(V)), ids, n, out);
+  gather_rows<V>(feat, row_stride, static_cast<uint32_t>(row_bytes / sizeof(V)), num_nodes, ids, n, out);
 }
 
 }  // namespace smfg_dev

@@ -1,7 +1,8 @@
 // libsmfg: sampled mini-batch preparation on gfx950 (MI355X).  Implements include/smfg.h.
 // This file is the host side (handles, validation, launch sequences); the kernels live in
 // device_common.h (launch parameters, Philox, dedup table), kernels_fast.h (fanouts up to 32),
-// kernels_wide.h (larger fanouts, full neighbourhoods), kernels_gather.h, kernels_aggregate.h.
+// kernels_wide.h (larger fanouts, full neighbourhoods), kernels_gather.h, kernels_aggregate.h,
+// kernels_validate.h (the optional check of the input arrays).
 //
 // One hop h of one batch is four launches (all batches of a call share each launch through
 // blockIdx.y):
@@ -43,6 +44,7 @@
 #include "kernels_aggregate.h"
 #include "kernels_fast.h"
 #include "kernels_gather.h"
+#include "kernels_validate.h"
 #include "kernels_wide.h"
 
 namespace {
@@ -225,6 +227,37 @@ int smfg_graph_create(smfg_graph_t** out, int64_t num_nodes, int64_t num_edges, 
 int smfg_graph_destroy(smfg_graph_t* g) {
   delete g;
   return SMFG_OK;
+}
+
+int smfg_graph_validate(const smfg_graph_t* g, uint32_t* h_flags, void* hip_stream) {
+  if (h_flags) *h_flags = 0;
+  if (!g) return SMFG_ERR_NULL_PTR;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int cur = 0;
+  (void)hipGetDevice(&cur);
+  if (cur != g->device) (void)hipSetDevice(g->device);
+  uint32_t* d_flags = nullptr;
+  uint32_t flags = 0;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_flags), sizeof(uint32_t));
+  if (e == hipSuccess) {
+    e = hipMemsetAsync(d_flags, 0, sizeof(uint32_t), st);
+    if (e == hipSuccess) {
+      k_validate_indptr<<<blocks_for(g->num_nodes, kThreads * 4, 4096), kThreads, 0, st>>>(g->indptr, g->num_nodes,
+                                                                                          g->num_edges, d_flags);
+      if (g->num_edges > 0)
+        k_validate_indices<<<blocks_for(g->num_edges, kThreads * 16, 8192), kThreads, 0, st>>>(
+            g->indices, g->num_edges, g->num_nodes, d_flags);
+      e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(&flags, d_flags, sizeof(uint32_t), hipMemcpyDeviceToHost, st);
+    const hipError_t es = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = es;
+    (void)hipFree(d_flags);
+  }
+  if (cur != g->device) (void)hipSetDevice(cur);
+  if (e != hipSuccess) return hip_err(e);
+  if (h_flags) *h_flags = flags;
+  return flags ? SMFG_ERR_BAD_GRAPH : SMFG_OK;
 }
 
 int smfg_graph_set_labels(smfg_graph_t* g, const void* d_labels, int32_t elem_bytes) {
@@ -550,7 +583,7 @@ int smfg_sample_mfg(const smfg_graph_t* g, smfg_workspace_t* ws, const int32_t* 
 int smfg_gather_many(const smfg_graph_t* g, const smfg_output_t* outs, int32_t num_batches, int32_t L,
                      void* hip_stream) {
   if (!g || !outs) return SMFG_ERR_NULL_PTR;
-  if (!g->feat) return SMFG_ERR_INVALID_ARG;
+  if (!g->feat || g->num_nodes < 1) return SMFG_ERR_INVALID_ARG;
   if (L < 1 || L > SMFG_MAX_LAYERS) return SMFG_ERR_TOO_MANY_LAYERS;
   if (num_batches < 1 || num_batches > SMFG_MAX_BATCHES) return SMFG_ERR_INVALID_ARG;
   Launch P;
@@ -588,7 +621,7 @@ int smfg_gather_many(const smfg_graph_t* g, const smfg_output_t* outs, int32_t n
 int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int64_t* d_num_rows,
                      int64_t max_rows, void* d_out, void* hip_stream) {
   if (!g || !d_node_ids || !d_num_rows || !d_out) return SMFG_ERR_NULL_PTR;
-  if (!g->feat) return SMFG_ERR_INVALID_ARG;
+  if (!g->feat || g->num_nodes < 1) return SMFG_ERR_INVALID_ARG;
   if (max_rows < 0 || max_rows >= (1ll << 31)) return SMFG_ERR_INVALID_ARG;
   if (max_rows == 0) return SMFG_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -600,11 +633,11 @@ int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int
   (void)hipGetDevice(&cur);
   if (cur != g->device) (void)hipSetDevice(g->device);
   switch (vb) {
-    case 16: k_gather_plain<u32x4><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
-    case 8: k_gather_plain<u32x2><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
-    case 4: k_gather_plain<uint32_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
-    case 2: k_gather_plain<uint16_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
-    default: k_gather_plain<uint8_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, d_node_ids, d_num_rows, max_rows, o); break;
+    case 16: k_gather_plain<u32x4><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    case 8: k_gather_plain<u32x2><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    case 4: k_gather_plain<uint32_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    case 2: k_gather_plain<uint16_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    default: k_gather_plain<uint8_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
   }
   hipError_t e = hipGetLastError();
   if (cur != g->device) (void)hipSetDevice(cur);
@@ -710,6 +743,7 @@ const char* smfg_strerror(int code) {
     case SMFG_ERR_TOO_MANY_SEEDS: return "more seeds than the workspace or output capacity";
     case SMFG_ERR_OOM: return "out of memory";
     case SMFG_ERR_CAPACITY: return "requested capacity exceeds what the workspace supports";
+    case SMFG_ERR_BAD_GRAPH: return "the graph's CSR arrays are inconsistent";
     case SMFG_ST_NODE_CAPACITY: return "device: node capacity exceeded";
     case SMFG_ST_EDGE_CAPACITY: return "device: edge capacity exceeded";
     case SMFG_ST_TABLE_FULL: return "device: dedup table full";

@@ -571,3 +571,57 @@ def test_randomised_small_dense_graphs():
                 assert_same(fetch(outs[b], len(fan)), gg.oracle.sample_mfg(seeds[b], fan, keys[b]), len(fan))
                 cases += 1
     assert cases > 300
+
+
+def test_graph_validate_names_what_is_broken(tiny):
+    """The optional CSR check: a sound graph passes; each planted defect sets its own bit.  The
+    check only reads the two arrays inside their stated lengths, so broken contents are safe."""
+    assert smfg.graph_validate(tiny[1].g) == 0
+    rng = np.random.default_rng(5)
+    indptr, indices = csr_from_adj(random_simple_graph(3000, 9, rng, hub=7))
+    n, m = len(indptr) - 1, len(indices)
+
+    def flags_of(ip, ix):
+        a = torch.from_numpy(np.ascontiguousarray(ip)).to(DEV)
+        b = torch.from_numpy(np.ascontiguousarray(ix)).to(DEV)
+        return smfg.graph_validate(smfg.graph_create(a, b, None))
+
+    assert flags_of(indptr, indices) == 0
+    ip = indptr.copy(); ip[0] = 1
+    assert flags_of(ip, indices) & smfg.BAD_INDPTR_START
+    ip = indptr.copy(); ip[n] = m - 1                      # last row shrinks: the end no longer matches
+    assert flags_of(ip, indices) == smfg.BAD_INDPTR_END
+    ip = indptr.copy(); ip[1500] = ip[1499] - 1            # one step backwards in the middle
+    assert flags_of(ip, indices) == smfg.BAD_INDPTR_ORDER
+    ip = indptr.copy(); ip[2000:] += 1 << 31               # a degree of 2^31 or more
+    assert flags_of(ip, indices) == smfg.BAD_INDPTR_ORDER | smfg.BAD_INDPTR_END
+    for bad in (-1, n, 2**31 - 1):
+        for where in (0, m // 2, m - 1):
+            ix = indices.copy(); ix[where] = bad
+            assert flags_of(indptr, ix) == smfg.BAD_INDEX_RANGE
+    ix = indices.copy(); ix[m - 1] = n - 1                 # the largest valid id
+    assert flags_of(indptr, ix) == 0
+    # no nodes, no edges
+    assert flags_of(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32)) == 0
+    assert flags_of(np.ones(1, dtype=np.int64), np.zeros(0, dtype=np.int32)) == (smfg.BAD_INDPTR_START
+                                                                                    | smfg.BAD_INDPTR_END)
+
+
+def test_gather_rows_never_reads_outside_the_feature_matrix():
+    """Row ids outside [0, num_nodes) are served from row 0; the valid rows around them are exact."""
+    rng = np.random.default_rng(11)
+    n, dim = 500, 24
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    feat = rng.standard_normal((n, dim)).astype(np.float16)
+    gg = GpuGraph(indptr, np.zeros(0, dtype=np.int32), feat)
+    ids_np = rng.integers(0, n, size=777).astype(np.int32)
+    bad_at = np.array([0, 5, 31, 32, 400, 776])
+    ids_np[bad_at] = np.array([-1, n, n + 12345, 2**31 - 1, -2**31, n], dtype=np.int32)
+    ids = torch.from_numpy(ids_np).to(DEV)
+    cnt = torch.tensor([ids.numel()], dtype=torch.int64, device=DEV)
+    out = torch.zeros((ids.numel(), dim), dtype=gg.feat.dtype, device=DEV)
+    smfg.gather_rows(gg.g, ids, cnt, ids.numel(), out)
+    torch.cuda.synchronize()
+    want_ids = ids_np.astype(np.int64)
+    want_ids[bad_at] = 0
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), feat[want_ids].view(np.uint16))
