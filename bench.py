@@ -253,7 +253,7 @@ def main():
                 o.c.counts = counts_all.data_ptr() + (W + c0 + b) * stride
                 n_dst, e_last = c[L - 1], c[2 * L]
                 cview = counts_all[W + c0 + b]
-                smfg.mean_aggregate(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.node_capacity, o.features,
+                smfg.mean_aggregate(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.indptr[L - 1].numel() - 1, o.features,
                                     agg_out, stream=streams[0])
                 agg_bytes += e_last * row_bytes + 4 * e_last + 4 * (n_dst + 1) + 4 * w.feat_dim * n_dst
         torch.cuda.synchronize()
@@ -305,7 +305,7 @@ def main():
             x = o.features
             for h in range(L - 1, -1, -1):
                 y = bufs[h % 2]
-                smfg.mean_aggregate(o.indptr[h], o.indices[h], o.counts[h:h + 1], cap, x, y)
+                smfg.mean_aggregate(o.indptr[h], o.indices[h], o.counts[h:h + 1], o.indptr[h].numel() - 1, x, y)
                 x = y
 
         def one_pass(with_consumer):

@@ -206,15 +206,18 @@ int smfg_gather_many(const smfg_graph_t *g, const smfg_output_t *outs, int32_t n
  * listing: x_target = x[:size[1]], conv((x, x_target), edge_index); equation 1 with agg = mean):
  *   out[i, :] = (1 / k_i) * sum over e in [indptr[i], indptr[i+1]) of float(x[indices[e], :]),
  * k_i = indptr[i+1] - indptr[i]; a destination without samples gets zeros.  i < *d_num_dst (a device
- * int64, e.g. &counts[h]); max_dst bounds the launch.  x: device, row-major [num_src x dim], dense,
- * elem_bytes 2 (IEEE half) or 4 (float); out: device float [max_dst x dim].  Sums run in float in
+ * int64, e.g. &counts[h]); max_dst bounds the launch (d_indptr holds at least max_dst + 1 entries,
+ * d_indices max_edges).  x: device, row-major [max_src x dim], dense, max_src >= 1,
+ * elem_bytes 2 (IEEE half) or 4 (float); out: device float [max_dst x dim].  Offsets beyond
+ * max_edges and source ids outside [0, max_src) - which only the unspecified arrays of a batch
+ * that ended with a status can hold - are clamped (row 0 is read): no read leaves the buffers.  Sums run in float in
  * slot order, then one division: the error of an output is at most k_i * 2^-24 times the mean of
  * the magnitudes added (k_i - 1 rounded additions and one rounded division).  Asynchronous on
  * hip_stream.
  */
-int smfg_mean_aggregate(const int32_t *d_indptr, const int32_t *d_indices, const int64_t *d_num_dst,
-                        int64_t max_dst, const void *d_x, int32_t dim, int32_t elem_bytes,
-                        float *d_out, void *hip_stream);
+int smfg_mean_aggregate(const int32_t *d_indptr, const int32_t *d_indices, int64_t max_edges,
+                        const int64_t *d_num_dst, int64_t max_dst, const void *d_x, int64_t max_src,
+                        int32_t dim, int32_t elem_bytes, float *d_out, void *hip_stream);
 
 /* Copies counts[0 .. 2L+2) to the host after synchronising the stream; returns SMFG_OK or, if the
  * status word is non-zero, its (positive) SMFG_ST_* value. */

@@ -83,7 +83,7 @@ def lib() -> ctypes.CDLL:
                                            ctypes.POINTER(u64), ctypes.POINTER(_Output), i32, vp]
         L.smfg_gather_rows.argtypes = [vp, vp, vp, i64, vp, vp]
         L.smfg_gather_many.argtypes = [vp, ctypes.POINTER(_Output), i32, i32, vp]
-        L.smfg_mean_aggregate.argtypes = [vp, vp, vp, i64, vp, i32, i32, vp, vp]
+        L.smfg_mean_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, i32, i32, vp, vp]
         L.smfg_read_counts.argtypes = [ctypes.POINTER(_Output), i32, ctypes.POINTER(i64), vp]
         L.smfg_profile_begin.argtypes = [i32, i32]
         L.smfg_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -312,10 +312,11 @@ def mean_aggregate(indptr: torch.Tensor, indices: torch.Tensor, num_dst: torch.T
     assert x.dim() == 2 and x.is_contiguous() and x.dtype in (torch.float16, torch.float32)
     assert out.dtype == torch.float32 and out.is_contiguous() and out.shape[1] == x.shape[1]
     assert out.shape[0] >= max_dst
+    assert indptr.numel() >= max_dst + 1
     rc = lib().smfg_mean_aggregate(ctypes.c_void_p(indptr.data_ptr()), ctypes.c_void_p(indices.data_ptr()),
-                                   ctypes.c_void_p(num_dst.data_ptr()), max_dst, ctypes.c_void_p(x.data_ptr()),
-                                   x.shape[1], x.element_size(), ctypes.c_void_p(out.data_ptr()),
-                                   _stream_ptr(stream))
+                                   indices.numel(), ctypes.c_void_p(num_dst.data_ptr()), max_dst,
+                                   ctypes.c_void_p(x.data_ptr()), x.shape[0], x.shape[1], x.element_size(),
+                                   ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc, "smfg_mean_aggregate")
 
 

@@ -644,11 +644,12 @@ int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int
   return hip_err(e);
 }
 
-int smfg_mean_aggregate(const int32_t* d_indptr, const int32_t* d_indices, const int64_t* d_num_dst,
-                        int64_t max_dst, const void* d_x, int32_t dim, int32_t elem_bytes, float* d_out,
-                        void* hip_stream) {
+int smfg_mean_aggregate(const int32_t* d_indptr, const int32_t* d_indices, int64_t max_edges,
+                        const int64_t* d_num_dst, int64_t max_dst, const void* d_x, int64_t max_src, int32_t dim,
+                        int32_t elem_bytes, float* d_out, void* hip_stream) {
   if (!d_indptr || !d_indices || !d_num_dst || !d_x || !d_out) return SMFG_ERR_NULL_PTR;
-  if (dim < 1 || (elem_bytes != 2 && elem_bytes != 4) || max_dst < 0 || max_dst >= (1ll << 31))
+  if (dim < 1 || (elem_bytes != 2 && elem_bytes != 4) || max_dst < 0 || max_dst >= (1ll << 31) || max_edges < 0 ||
+      max_edges >= (1ll << 31) || max_src < 1 || max_src >= (1ll << 31))
     return SMFG_ERR_INVALID_ARG;
   if (max_dst == 0) return SMFG_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -659,17 +660,17 @@ int smfg_mean_aggregate(const int32_t* d_indptr, const int32_t* d_indices, const
     if (elem_bytes == 2) {
       const _Float16* x = static_cast<const _Float16*>(d_x);
       if (dim % 8 == 0 && ax % 16 == 0)
-        k_mean_aggregate<_Float16, 8><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+        k_mean_aggregate<_Float16, 8><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
       else if (dim % 2 == 0 && ax % 4 == 0)
-        k_mean_aggregate<_Float16, 2><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+        k_mean_aggregate<_Float16, 2><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
       else
-        k_mean_aggregate<_Float16, 1><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+        k_mean_aggregate<_Float16, 1><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
     } else {
       const float* x = static_cast<const float*>(d_x);
       if (dim % 4 == 0 && ax % 16 == 0)
-        k_mean_aggregate<float, 4><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+        k_mean_aggregate<float, 4><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
       else
-        k_mean_aggregate<float, 1><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, d_num_dst, max_dst, x, dim, d_out);
+        k_mean_aggregate<float, 1><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
     }
   }
   return hip_err(hipGetLastError());

@@ -328,7 +328,7 @@ def test_mean_aggregate_consumer(dim, dtype):
     for h in (2, 1, 0):
         n_dst = res["n"][h]
         y = torch.full((out.node_capacity, dim), float("nan"), dtype=torch.float32, device=DEV)
-        smfg.mean_aggregate(out.indptr[h], out.indices[h], out.counts[h:h + 1], out.node_capacity, x_gpu, y)
+        smfg.mean_aggregate(out.indptr[h], out.indices[h], out.counts[h:h + 1], out.indptr[h].numel() - 1, x_gpu, y)
         torch.cuda.synchronize()
         mean, mag = oracle.mean_aggregate(ref.indptr[h], ref.indices[h], np.ascontiguousarray(x_ref))
         got = y[:n_dst].cpu().numpy().astype(np.float64)
@@ -625,3 +625,26 @@ def test_gather_rows_never_reads_outside_the_feature_matrix():
     want_ids = ids_np.astype(np.int64)
     want_ids[bad_at] = 0
     assert np.array_equal(out.cpu().numpy().view(np.uint16), feat[want_ids].view(np.uint16))
+
+
+def test_mean_aggregate_clamps_stray_offsets_and_ids():
+    """A block left behind by a failed batch may hold anything: offsets are clamped to the indices
+    array and ids outside x read row 0.  The rows that are sound keep their exact means."""
+    rng = np.random.default_rng(3)
+    n_src, n_dst, dim, m = 40, 6, 8, 20
+    x = rng.standard_normal((n_src, dim)).astype(np.float32)
+    indptr = np.array([0, 3, 7, 7, 12, 18, 31], dtype=np.int32)        # last row runs past the 20 edges
+    indices = rng.integers(0, n_src, size=m).astype(np.int32)
+    indices[[1, 8, 13]] = [-5, n_src, 2**31 - 1]                        # stray ids -> row 0
+    y = torch.full((n_dst, dim), float("nan"), dtype=torch.float32, device=DEV)
+    smfg.mean_aggregate(torch.from_numpy(indptr).to(DEV), torch.from_numpy(indices).to(DEV),
+                        torch.tensor([n_dst], dtype=torch.int64, device=DEV), n_dst,
+                        torch.from_numpy(x).to(DEV), y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    ids = indices.astype(np.int64)
+    ids[(ids < 0) | (ids >= n_src)] = 0
+    for i in range(n_dst):
+        a, b = int(indptr[i]), min(int(indptr[i + 1]), m)
+        want = x[ids[a:b]].astype(np.float64).mean(axis=0) if b > a else np.zeros(dim)
+        assert np.allclose(got[i], want, rtol=0, atol=1e-5), i
