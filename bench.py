@@ -238,6 +238,25 @@ def main():
     alone_ms, alone_launches = smfg.profile_end()["gather"]
     alone_gbs = 2 * row_bytes * rows_alone / (alone_ms * 1e-3) / 1e9 if alone_ms > 0 else 0.0
 
+    # What a plain device-to-device copy reaches on this machine (1 GiB in, 1 GiB out, nothing else
+    # running): the achievable ceiling next to the published peak.
+    copy_gbs = 0.0
+    try:
+        a = torch.empty(1 << 28, dtype=torch.int32, device=dev).fill_(1)
+        b = torch.empty_like(a)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        b.copy_(a)
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(8):
+            b.copy_(a)
+        ev[1].record()
+        torch.cuda.synchronize()
+        copy_gbs = 8 * 2 * (1 << 30) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+        del a, b
+    except torch.OutOfMemoryError:
+        pass
+
     # A consumer of the prepared batches (not part of the timed path): GraphSAGE mean aggregation
     # over the outermost block of the batches of the last launch set.
     consumer = None
@@ -287,7 +306,10 @@ def main():
                              "launch repeated right after with nothing else running",
                      "alone_achieved": alone_gbs, "alone_frac": alone_gbs / HBM_PEAK_GBS,
                      "alone_avg_launch_ms": alone_ms / max(1, alone_launches),
-                     "algorithmic_bytes_per_launch": gather_bytes / max(1, gather_launches)},
+                     "algorithmic_bytes_per_launch": gather_bytes / max(1, gather_launches),
+                     "device_copy_GBps": copy_gbs,
+                     "alone_frac_of_device_copy": alone_gbs / copy_gbs if copy_gbs > 0 else None,
+                     "read_only_half_GBps": gather_gbs / 2},
     }
 
     if consumer is not None:
