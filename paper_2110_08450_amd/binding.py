@@ -224,6 +224,16 @@ class Output:
     c: _Output = field(repr=False, default=None)
 
 
+def mfg_blocks(out: Output, counts: Sequence[int]):
+    """Views of one prepared batch in the order a layer-by-layer consumer walks it (Appendix C,
+    GraphSAGE listing): outermost hop first.  `counts` is what read_counts returned.  Each item is
+    (indptr [n_dst + 1], indices [E], (n_src, n_dst)); the destinations of a block are the first
+    n_dst of its n_src source nodes.  No copies."""
+    L = out.L
+    n, e = counts[:L + 1], counts[L + 1:2 * L + 1]
+    return [(out.indptr[h][:n[h] + 1], out.indices[h][:e[h]], (n[h + 1], n[h])) for h in range(L - 1, -1, -1)]
+
+
 def alloc_output(g: Graph, max_seeds: int, fanouts: Sequence[int], node_capacity: Optional[int] = None,
                  edge_capacity: Optional[Sequence[int]] = None, with_features: bool = True) -> Output:
     """torch.empty device buffers sized to the worst case unless capacities are given."""

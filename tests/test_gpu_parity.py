@@ -648,3 +648,26 @@ def test_mean_aggregate_clamps_stray_offsets_and_ids():
         a, b = int(indptr[i]), min(int(indptr[i + 1]), m)
         want = x[ids[a:b]].astype(np.float64).mean(axis=0) if b > a else np.zeros(dim)
         assert np.allclose(got[i], want, rtol=0, atol=1e-5), i
+
+
+def test_blocks_in_consumer_order(tiny):
+    """mfg_blocks hands out trimmed views, outermost hop first, whose shapes chain."""
+    w, gg, batches = tiny
+    seeds = batches[1].to(DEV)
+    L = len(w.fanouts)
+    ws = smfg.workspace_create(gg.g, seeds.numel(), w.fanouts)
+    out = smfg.alloc_output(gg.g, seeds.numel(), w.fanouts)
+    smfg.sample_mfg(gg.g, ws, seeds, w.fanouts, 77, out)
+    counts = smfg.read_counts(out)
+    ref = gg.oracle.sample_mfg(batches[1].numpy(), w.fanouts, 77)
+    blocks = smfg.mfg_blocks(out, counts)
+    assert len(blocks) == L
+    n_src_prev = None
+    for j, (indptr, indices, (n_src, n_dst)) in enumerate(blocks):
+        h = L - 1 - j
+        assert np.array_equal(indptr.cpu().numpy(), ref.indptr[h]) and np.array_equal(indices.cpu().numpy(), ref.indices[h])
+        assert indptr.data_ptr() == out.indptr[h].data_ptr()          # a view, not a copy
+        assert (n_src, n_dst) == (int(ref.counts[h + 1]), int(ref.counts[h]))
+        assert n_src_prev is None or n_src == n_src_prev[1]          # dst of the outer block = src of the next
+        n_src_prev = (n_src, n_dst)
+    assert blocks[0][2][0] == counts[L] and blocks[-1][2][1] == seeds.numel()
