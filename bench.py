@@ -108,6 +108,7 @@ def main():
                     help="1: gather of launch set i runs on a second stream while set i+1 is sampled (two "
                          "buffer sets); 0: every launch set runs start to end on one stream (see --streams)")
     ap.add_argument("--feat-dim", type=int, default=0, help="experiment: override the feature width")
+    ap.add_argument("--depth", type=int, default=2, help="buffer sets of the pipelined run")
     ap.add_argument("--row-stride", type=int, default=0,
                     help="experiment: feature row stride in bytes (>= row bytes; 0 = dense rows)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
@@ -160,7 +161,8 @@ def main():
     scap = min(graph.num_edges, (1 << 30) - 1) if wide else 0   # a hop never has more samples than the graph has edges
     if args.pipeline:
         from paper_2110_08450_amd.pipeline import BatchPipeline
-        pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G, sample_capacity=scap)
+        pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G, sample_capacity=scap,
+                             depth=max(2, args.depth))
         S, streams, wss, outs = 2, [pipe.s_sample, pipe.s_gather], pipe.wss, pipe.outs
     else:
         S = max(1, args.streams)
@@ -181,7 +183,7 @@ def main():
     def run_pipelined(first, n):
         for c in range(first, first + n, G):
             k = min(G, first + n - c)
-            q = sets_issued[0] % 2
+            q = sets_issued[0] % pipe.depth
             sets_issued[0] += 1
             last_call[q] = (c, k)
             idx = [(c + b) % len(batches) for b in range(k)]
