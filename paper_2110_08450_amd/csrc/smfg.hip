@@ -661,6 +661,8 @@ int smfg_mean_aggregate(const int32_t* d_indptr, const int32_t* d_indices, int64
       const _Float16* x = static_cast<const _Float16*>(d_x);
       if (dim % 8 == 0 && ax % 16 == 0)
         k_mean_aggregate<_Float16, 8><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
+      else if (dim % 4 == 0 && ax % 8 == 0)
+        k_mean_aggregate<_Float16, 4><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
       else if (dim % 2 == 0 && ax % 4 == 0)
         k_mean_aggregate<_Float16, 2><<<gb, kThreads, 0, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, d_out);
       else

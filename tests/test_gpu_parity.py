@@ -301,7 +301,8 @@ def test_pipelined_hand_off_matches_oracle():
 
 
 @pytest.mark.parametrize("dim,dtype", [(128, np.float16), (100, np.float16), (33, np.float16),
-                                       (128, np.float32), (5, np.float32)])
+                                       (128, np.float32), (5, np.float32), (34, np.float16), (300, np.float16),
+                                       (272, np.float16), (200, np.float32)])
 def test_mean_aggregate_consumer(dim, dtype):
     """GraphSAGE mean aggregation over the blocks of a sampled batch, outermost hop first, feeding
     each layer's output (cast back to the input type) to the next block, as the model listing of
@@ -671,3 +672,43 @@ def test_blocks_in_consumer_order(tiny):
         assert n_src_prev is None or n_src == n_src_prev[1]          # dst of the outer block = src of the next
         n_src_prev = (n_src, n_dst)
     assert blocks[0][2][0] == counts[L] and blocks[-1][2][1] == seeds.numel()
+
+
+@pytest.mark.parametrize("fanouts", [(-1,), (40, 2)])
+def test_mean_aggregate_long_and_empty_rows(fanouts):
+    """Blocks of the wide path: a destination with 700 samples next to destinations with none,
+    one or a few, so the sums cross many load rounds and the groups of neighbouring destinations
+    end at different places."""
+    rng = np.random.default_rng(17)
+    adj = random_simple_graph(2500, 6, rng, hub=700)
+    for v in (10, 11, 500):
+        adj[v] = []
+    adj = [[u for u in row if u not in (10, 11, 500)] for row in adj]
+    indptr, indices = csr_from_adj(adj)
+    dim = 64
+    feat = (rng.standard_normal((2500, dim)) * 3).astype(np.float16)
+    gg = GpuGraph(indptr, indices, feat)
+    hub = int(np.argmax(np.diff(indptr)))
+    seeds = np.unique(np.concatenate([[10, hub, 11, 500], rng.choice(2500, size=333, replace=False)])).astype(np.int32)
+    rng.shuffle(seeds)
+    L = len(fanouts)
+    m = len(indices)
+    ws = smfg.workspace_create(gg.g, len(seeds), fanouts, sample_capacity=m)
+    out = smfg.alloc_output(gg.g, len(seeds), fanouts, edge_capacity=[m] * L)
+    smfg.sample_mfg(gg.g, ws, torch.from_numpy(seeds).to(DEV), fanouts, 5, out)
+    res = fetch(out, L)
+    ref = gg.oracle.sample_mfg(seeds, fanouts, 5)
+    assert_same(res, ref, L)
+    x_ref = ref.features.view(np.float16).reshape(-1, dim)
+    h = 0                      # the block of the seeds: its sources are a prefix of the node list
+    n_dst = res["n"][h]
+    y = torch.full((out.node_capacity, dim), float("nan"), dtype=torch.float32, device=DEV)
+    smfg.mean_aggregate(out.indptr[h], out.indices[h], out.counts[h:h + 1], out.indptr[h].numel() - 1, out.features, y)
+    torch.cuda.synchronize()
+    mean, mag = oracle.mean_aggregate(ref.indptr[h], ref.indices[h], np.ascontiguousarray(x_ref))
+    got = y[:n_dst].cpu().numpy().astype(np.float64)
+    k = np.diff(ref.indptr[h])
+    assert k.max() >= 40 and (k == 0).sum() >= 1
+    assert np.isnan(y[n_dst:].cpu().numpy()).all()
+    assert (np.abs(got - mean) <= np.maximum(k, 1)[:, None] * 2.0 ** -24 * mag).all()
+    assert (got[k == 0] == 0).all()
