@@ -29,8 +29,7 @@ struct BatchCtx {
   int64_t lostto_entries;
   int32_t* gsrc;         // per (destination, s): global id of the sampled neighbour
   int32_t* rowk;         // samples per destination
-  uint32_t* rowmask;     // first-appearance bits per destination
-  int32_t* newrank;      // new nodes of the tile before this destination's first new node
+  uint2* rowmn;          // per destination: .x first-appearance bits, .y new nodes of the tile before its first new node
   int32_t* rowoff;       // samples of the tile before this destination
   uint64_t* tile_sums;   // per tile: (edges << 32 | new nodes), later their exclusive scan
   int64_t* rowstart;     // wide path: first CSR position of the destination's row

@@ -190,9 +190,8 @@ __global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
     unsigned long long total;
     const unsigned long long pre = block_exscan(x, lds, total);
     if (tr < nrows) {
-      B.rowmask[i0 + tr] = m;
+      B.rowmn[i0 + tr] = make_uint2(m, static_cast<uint32_t>(pre & 0xFFFFFFFFull));
       B.rowoff[i0 + tr] = static_cast<int32_t>(pre >> 32);
-      B.newrank[i0 + tr] = static_cast<int32_t>(pre & 0xFFFFFFFFull);
     }
     if (tr == 0) B.tile_sums[tile] = total;
   }
@@ -245,11 +244,11 @@ __global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
     __syncthreads();
     if (tr < nrows) {
       const uint32_t off = static_cast<uint32_t>(tpre >> 32) + static_cast<uint32_t>(B.rowoff[i0 + tr]);
+      const uint2 mn = B.rowmn[i0 + tr];
       k_lds[tr] = B.rowk[i0 + tr];
-      mask_lds[tr] = B.rowmask[i0 + tr];
+      mask_lds[tr] = mn.x;
       off_lds[tr] = off;
-      rank_lds[tr] = static_cast<uint32_t>(n) + static_cast<uint32_t>(tpre & 0xFFFFFFFFull) +
-                     static_cast<uint32_t>(B.newrank[i0 + tr]);
+      rank_lds[tr] = static_cast<uint32_t>(n) + static_cast<uint32_t>(tpre & 0xFFFFFFFFull) + mn.y;
       B.blk_indptr[i0 + tr] = static_cast<int32_t>(off);
     } else {
       k_lds[tr] = 0;
@@ -266,36 +265,58 @@ __global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
         e[u] = idx < cnt ? B.ent[pos0 + idx] : 0u;
         g[u] = idx < cnt ? static_cast<uint32_t>(B.gsrc[pos0 + idx]) : 0u;
       }
+      // Samples that repeat a node found earlier in this hop point at the position q of another
+      // sample of it.  The row record of q is fetched for all U samples of the thread before any
+      // is used (a sample without such a pointer fetches the tile's first row instead), so the
+      // scattered reads of a thread overlap.
+      uint32_t r[U], sl[U], q[U], qi[U];
+      bool live[U], dup[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t idx = base + u * kThreads;
-        if (idx >= cnt) continue;
-        uint32_t r, sl;
-        div.split(idx, r, sl);
-        if (sl >= static_cast<uint32_t>(k_lds[r])) continue;
+        r[u] = 0u;
+        sl[u] = 0u;
+        if (idx < cnt) div.split(idx, r[u], sl[u]);
+        live[u] = idx < cnt && sl[u] < static_cast<uint32_t>(k_lds[r[u]]);
         const uint32_t tag = e[u] & kTagMask;
+        dup[u] = live[u] && tag != 0u && tag != kSlot;
+        q[u] = dup[u] ? (e[u] & ~kTagMask) : pos0;
+        qi[u] = q[u] / d;
+      }
+      uint2 mn[U];
+      uint32_t ts[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        mn[u] = B.rowmn[qi[u]];
+        ts[u] = static_cast<uint32_t>(B.tile_sums[qi[u] / kTileRows] & 0xFFFFFFFFull);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
         uint32_t local = e[u];
-        if (tag == kSlot) {  // first appearance: rank among the new nodes of this hop
-          local = rank_lds[r] + __popc(mask_lds[r] & ((1u << sl) - 1u));
+        if ((e[u] & kTagMask) == kSlot) {  // first appearance: rank among the new nodes of this hop
+          local = rank_lds[r[u]] + __popc(mask_lds[r[u]] & ((1u << sl[u]) - 1u));
           B.node_ids[local] = static_cast<int32_t>(g[u]);
           if (!last) B.table[e[u] & ~kTagMask] = (static_cast<uint64_t>(g[u]) << 32) | local;
-        } else if (tag != 0u) {  // kPend: same node as the sample at position q < own position
-          uint32_t q = e[u] & ~kTagMask;
+        } else if (dup[u]) {
+          uint32_t qq = q[u], qqi = qi[u];
+          uint2 m = mn[u];
+          uint32_t t = ts[u];
           for (;;) {
-            const uint32_t qi = q / d, qs = q - qi * d;
-            const uint32_t m = B.rowmask[qi];
-            if ((m >> qs) & 1u) {  // q is the node's first appearance
-              local = static_cast<uint32_t>(n) +
-                      static_cast<uint32_t>(B.tile_sums[qi / kTileRows] & 0xFFFFFFFFull) +
-                      static_cast<uint32_t>(B.newrank[qi]) + __popc(m & ((1u << qs) - 1u));
+            const uint32_t qs = qq - qqi * d;
+            if ((m.x >> qs) & 1u) {  // qq is the node's first appearance
+              local = static_cast<uint32_t>(n) + t + m.y + __popc(m.x & ((1u << qs) - 1u));
               break;
             }
-            const uint32_t nxt = B.ent[q] & ~kTagMask;  // strictly smaller position
-            if (nxt >= q) break;                        // cannot happen; guards the loop
-            q = nxt;
+            const uint32_t nxt = B.ent[qq] & ~kTagMask;  // strictly smaller position
+            if (nxt >= qq) break;                        // cannot happen; guards the loop
+            qq = nxt;
+            qqi = qq / d;
+            m = B.rowmn[qqi];
+            t = static_cast<uint32_t>(B.tile_sums[qqi / kTileRows] & 0xFFFFFFFFull);
           }
         }
-        B.blk_indices[off_lds[r] + sl] = static_cast<int32_t>(local);
+        B.blk_indices[off_lds[r[u]] + sl[u]] = static_cast<int32_t>(local);
       }
     }
   }

@@ -133,8 +133,7 @@ struct smfg_workspace {
   uint32_t* lostto;
   int32_t* gsrc;
   int32_t* rowk;
-  uint32_t* rowmask;
-  int32_t* newrank;
+  uint2* rowmn;
   int32_t* rowoff;
   uint64_t* tile_sums;
   int64_t* rowstart;
@@ -361,8 +360,7 @@ int smfg_workspace_create_sized(smfg_workspace_t** out, const smfg_graph_t* g, i
   ws->lostto = reinterpret_cast<uint32_t*>(p); p += b_slot;
   ws->gsrc = reinterpret_cast<int32_t*>(p); p += b_slot;
   ws->rowk = reinterpret_cast<int32_t*>(p); p += b_rowk;
-  ws->rowmask = reinterpret_cast<uint32_t*>(p); p += b_mask;
-  ws->newrank = reinterpret_cast<int32_t*>(p); p += b_rowk;
+  ws->rowmn = reinterpret_cast<uint2*>(p); p += b_mask + b_rowk;
   ws->rowoff = reinterpret_cast<int32_t*>(p); p += b_rowk;
   ws->tile_sums = reinterpret_cast<uint64_t*>(p); p += b_tiles;
   ws->rowstart = reinterpret_cast<int64_t*>(p); p += b_start;
@@ -466,8 +464,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     B.lostto_entries = w->slot_entries;
     B.gsrc = w->gsrc;
     B.rowk = w->rowk;
-    B.rowmask = w->rowmask;
-    B.newrank = w->newrank;
+    B.rowmn = w->rowmn;
     B.rowoff = w->rowoff;
     B.tile_sums = w->tile_sums;
     B.rowstart = w->rowstart;
