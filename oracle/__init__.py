@@ -46,6 +46,11 @@ def _configure(lib):
         lib.oracle_mean_aggregate.restype = ctypes.c_int32
         lib.oracle_mean_aggregate.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
                                               ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_sage_layer.restype = ctypes.c_int32
+        lib.oracle_sage_layer.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_sample_mfg.restype = ctypes.c_int32
         lib.oracle_sample_mfg.argtypes = [
             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p,
@@ -120,6 +125,31 @@ def mean_aggregate(indptr: np.ndarray, indices: np.ndarray, x: np.ndarray):
     if rc != 0:
         raise ValueError(f"oracle_mean_aggregate: {rc}")
     return mean, mag
+
+
+def sage_layer(indptr: np.ndarray, indices: np.ndarray, x: np.ndarray, w: np.ndarray,
+               bias: Optional[np.ndarray], relu: bool):
+    """(out, mag) in float64 for one GraphSAGE layer over a block: x [n_src x dim] float16/float32,
+    w [out_dim x 2 dim] (columns [0, dim) act on the node's own row, [dim, 2 dim) on the mean),
+    bias [out_dim] or None."""
+    indptr = np.ascontiguousarray(indptr, dtype=np.int32)
+    indices = np.ascontiguousarray(indices, dtype=np.int32)
+    assert x.ndim == 2 and x.flags["C_CONTIGUOUS"] and x.dtype in (np.float16, np.float32)
+    n, dim = len(indptr) - 1, x.shape[1]
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    assert w.ndim == 2 and w.shape[1] == 2 * dim
+    out_dim = w.shape[0]
+    b = None if bias is None else np.ascontiguousarray(bias, dtype=np.float64)
+    assert b is None or b.shape == (out_dim,)
+    tmp = np.zeros((2, max(1, n), dim), dtype=np.float64)
+    out = np.zeros((n, out_dim), dtype=np.float64)
+    mag = np.zeros((n, out_dim), dtype=np.float64)
+    rc = _load().oracle_sage_layer(indptr.ctypes.data, indices.ctypes.data, n, x.ctypes.data, dim, x.itemsize,
+                                   w.ctypes.data, None if b is None else b.ctypes.data, out_dim, int(bool(relu)),
+                                   tmp[0].ctypes.data, tmp[1].ctypes.data, out.ctypes.data, mag.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"oracle_sage_layer: {rc}")
+    return out, mag
 
 
 @dataclass

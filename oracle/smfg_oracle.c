@@ -6,7 +6,8 @@
  * one-hop message-flow-graph construction with its ordered global->local map (the MFG
  * construction algorithm, procedure OneHopMFG), chained over hops (section 4.1), and the
  * slice xs = x[ids] of Listing 1; plus the label slice of Listing 1 and, as a consumer of the
- * blocks, the mean aggregation of equation 1 / the GraphSAGE listing of Appendix C.
+ * blocks, the mean aggregation and the whole GraphSAGE layer (mean, linear layer on the
+ * concatenation, ReLU) of equation 1 / section 2.1 / the GraphSAGE listing of Appendix C.
  *
  * Only tests, the smoke check and the CPU-baseline leg of the benchmark may use this file.
  * It shares nothing with the HIP library: no header, no table, no helper.
@@ -156,6 +157,44 @@ int32_t oracle_mean_aggregate(const int32_t *indptr, const int32_t *indices, int
       }
       mean[i * dim + c] = k > 0 ? s / k : 0.0;
       mag[i * dim + c] = k > 0 ? a / k : 0.0;
+    }
+  }
+  return ORACLE_OK;
+}
+
+/* One GraphSAGE layer over a block (equation 1 with the choices section 2.1 names for GraphSAGE:
+ * agg = mean of the sampled neighbours, upd = a linear layer on the concatenation of the node's
+ * own row and that mean; the model listing of Appendix C applies a ReLU after every layer but the
+ * last).  The destinations of a block are its first num_dst source rows, so the node's own row is
+ * x[i]:
+ *   out[i, j] = act(bias[j] + sum_c w[j, c] x[i, c] + sum_c w[j, dim + c] mean[i, c]),
+ * w row-major [out_dim x 2 dim] (the layout of a linear layer's weight), bias [out_dim] or NULL,
+ * act = max(., 0) if relu else the identity.  mag[i, j] = |bias[j]| + sum_c |w[j, c]| |x[i, c]| +
+ * sum_c |w[j, dim + c]| mag_mean[i, c] is the scale for a float error bound.  All in double;
+ * mean_tmp, mag_tmp: caller scratch [num_dst x dim]. */
+int32_t oracle_sage_layer(const int32_t *indptr, const int32_t *indices, int64_t num_dst,
+                          const void *x, int32_t dim, int32_t elem_bytes, const double *w,
+                          const double *bias, int32_t out_dim, int32_t relu, double *mean_tmp,
+                          double *mag_tmp, double *out, double *mag) {
+  if (!w || !out || !mag || !mean_tmp || !mag_tmp || out_dim < 1) return ORACLE_ERR_ARG;
+  int32_t rc = oracle_mean_aggregate(indptr, indices, num_dst, x, dim, elem_bytes, mean_tmp, mag_tmp);
+  if (rc != ORACLE_OK) return rc;
+  for (int64_t i = 0; i < num_dst; ++i) {
+    for (int32_t j = 0; j < out_dim; ++j) {
+      const double *wj = w + (int64_t)j * 2 * dim;
+      double s = bias ? bias[j] : 0.0;
+      double a = s < 0 ? -s : s;
+      for (int32_t c = 0; c < dim; ++c) {
+        int64_t at = i * dim + c;
+        double own = elem_bytes == 2 ? oracle_half_to_double(((const uint16_t *)x)[at])
+                                     : (double)((const float *)x)[at];
+        double w_own = wj[c], w_agg = wj[dim + c];
+        s += w_own * own + w_agg * mean_tmp[at];
+        a += (w_own < 0 ? -w_own : w_own) * (own < 0 ? -own : own) +
+             (w_agg < 0 ? -w_agg : w_agg) * mag_tmp[at];
+      }
+      out[i * out_dim + j] = (relu && s < 0.0) ? 0.0 : s;
+      mag[i * out_dim + j] = a;
     }
   }
   return ORACLE_OK;

@@ -12,6 +12,9 @@ int32_t oracle_sample_mfg(int64_t, const int64_t *, const int32_t *, const void 
 int32_t oracle_slice_labels(const void *, int32_t, int64_t, const int32_t *, int32_t, void *);
 int32_t oracle_mean_aggregate(const int32_t *, const int32_t *, int64_t, const void *, int32_t, int32_t,
                               double *, double *);
+int32_t oracle_sage_layer(const int32_t *, const int32_t *, int64_t, const void *, int32_t, int32_t,
+                          const double *, const double *, int32_t, int32_t, double *, double *, double *,
+                          double *);
 int32_t oracle_sample_positions(uint32_t, int32_t, uint64_t, uint32_t, uint32_t, uint32_t *);
 
 static uint64_t rng_state = 88172645463325252ull;
@@ -80,6 +83,16 @@ int main(void) {
           double *mean = malloc(sizeof(double) * 6 * (size_t)(counts[L - 1] + 1));
           double *mag = malloc(sizeof(double) * 6 * (size_t)(counts[L - 1] + 1));
           if (oracle_mean_aggregate(bp[L - 1], bi[L - 1], counts[L - 1], out_feat, 6, 4, mean, mag) != 0) return 1;
+          {                       /* a layer with 5 outputs over the same block */
+            double w[5 * 12], bias[5];
+            for (int q = 0; q < 5 * 12; ++q) w[q] = (double)(rnd() % 17) - 8.0;
+            for (int q = 0; q < 5; ++q) bias[q] = (double)(rnd() % 5) - 2.0;
+            double *lo = malloc(sizeof(double) * 5 * (size_t)(counts[L - 1] + 1));
+            double *lm = malloc(sizeof(double) * 5 * (size_t)(counts[L - 1] + 1));
+            if (oracle_sage_layer(bp[L - 1], bi[L - 1], counts[L - 1], out_feat, 6, 4, w, bias, 5, 1, mean, mag,
+                                  lo, lm) != 0) return 1;
+            free(lo); free(lm);
+          }
           free(mean); free(mag);
           ++checked;
         }

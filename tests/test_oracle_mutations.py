@@ -46,6 +46,15 @@ MUTATIONS = [
     ("mean divides by k + 1", "mean[i * dim + c] = k > 0 ? s / k : 0.0;", "mean[i * dim + c] = k > 0 ? s / (k + 1) : 0.0;"),
     ("mean reads the destination's own row", "int64_t at = (int64_t)indices[e] * dim + c;",
      "int64_t at = (int64_t)i * dim + c;"),
+    ("layer: weight halves swapped", "double w_own = wj[c], w_agg = wj[dim + c];",
+     "double w_own = wj[dim + c], w_agg = wj[c];"),
+    ("layer: weight read transposed", "const double *wj = w + (int64_t)j * 2 * dim;",
+     "const double *wj = w + (int64_t)j;"),
+    ("layer: bias dropped", "double s = bias ? bias[j] : 0.0;", "double s = 0.0;"),
+    ("layer: ReLU never applied", "(relu && s < 0.0) ? 0.0 : s;", "s;"),
+    ("layer: ReLU always applied", "(relu && s < 0.0) ? 0.0 : s;", "(s < 0.0) ? 0.0 : s;"),
+    ("layer: own row taken from the mean", "s += w_own * own + w_agg * mean_tmp[at];",
+     "s += w_own * mean_tmp[at] + w_agg * mean_tmp[at];"),
     ("half exponent bias off by one", "int e = ex - 15;", "int e = ex - 14;"),
     ("half subnormals scaled as normals", "v = (double)man / 1024.0 / 16384.0;", "v = (double)man / 1024.0 / 32768.0;"),
     ("label taken by position instead of node", "(const char *)labels + (int64_t)seeds[i] * elem_bytes",
@@ -73,6 +82,8 @@ def _pins():
     yield lambda: pins.test_label_slice_is_plain_indexing(np.int32)
     yield pins.test_half_decoding_matches_numpy_for_every_bit_pattern
     yield lambda: pins.test_mean_aggregate_equals_sparse_matrix_product(np.float16)
+    yield lambda: pins.test_sage_layer_equals_dense_linear_algebra(np.float16, True, True)
+    yield lambda: pins.test_sage_layer_equals_dense_linear_algebra(np.float32, False, True)
     yield lambda: pins.test_chi_square_uniform_subsets(8, 3)
     yield lambda: pins.test_chi_square_uniform_subsets(40, 15)
 

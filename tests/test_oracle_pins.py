@@ -378,6 +378,48 @@ def test_mean_aggregate_equals_sparse_matrix_product(dtype):
         x = mean.astype(dtype)           # next layer's input has n_dst rows: the prefix property
 
 
+@pytest.mark.parametrize("dtype,relu,with_bias", [(np.float16, True, True), (np.float32, False, True),
+                                                  (np.float16, False, False)])
+def test_sage_layer_equals_dense_linear_algebra(dtype, relu, with_bias):
+    """A GraphSAGE layer over a block written as matrix algebra: with M = D^-1 A X the neighbour
+    means (scipy.sparse) and X_t the first n_dst rows of X, out = act([X_t | M] W^T + b) (numpy
+    matmul in float64).  out_dim differs from 2 dim and the two halves of W differ in scale, so a
+    transposed or swapped weight shows; half of the biases are large and negative, so the ReLU
+    decides entries."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(21)
+    adj = random_simple_graph(300, 9, rng)
+    adj[5] = []
+    adj = [[u for u in row if u != 5] for row in adj]
+    indptr, indices = csr_from_adj(adj)
+    orc = oracle.Oracle(indptr, indices)
+    seeds = np.concatenate([[5], rng.choice(np.arange(6, 300), size=40, replace=False)]).astype(np.int32)
+    r = orc.sample_mfg(seeds, (4, 3), 17)
+    dim, out_dim = 12, 7
+    x = (rng.standard_normal((r.num_nodes[2], dim)) * 3).astype(dtype)
+    w = rng.standard_normal((out_dim, 2 * dim))
+    w[:, dim:] *= 5.0
+    b = rng.standard_normal(out_dim) * 4 - np.where(np.arange(out_dim) % 2 == 0, 30.0, 0.0) if with_bias else None
+    h = 1
+    n_dst, n_src = r.num_nodes[h], r.num_nodes[h + 1]
+    xs = np.ascontiguousarray(x[:n_src])
+    out, mag = oracle.sage_layer(r.indptr[h], r.indices[h], xs, w, b, relu)
+    k = np.diff(r.indptr[h]).astype(np.float64)
+    a = sp.csr_matrix((np.ones(len(r.indices[h])), r.indices[h], r.indptr[h]), shape=(n_dst, n_src))
+    inv = np.divide(1.0, k, out=np.zeros_like(k), where=k > 0)
+    x64 = xs.astype(np.float64)
+    m = sp.diags(inv) @ (a @ x64)
+    m_abs = sp.diags(inv) @ (a @ np.abs(x64))
+    want = np.concatenate([x64[:n_dst], m], axis=1) @ w.T + (b if with_bias else 0.0)
+    want_mag = np.concatenate([np.abs(x64[:n_dst]), m_abs], axis=1) @ np.abs(w).T + (np.abs(b) if with_bias else 0.0)
+    if relu:
+        assert (want < 0).any() and (want > 0).any()
+        want = np.maximum(want, 0.0)
+    assert out.shape == (n_dst, out_dim)
+    assert np.allclose(out, want, rtol=1e-12, atol=1e-12)
+    assert np.allclose(mag, want_mag, rtol=1e-12, atol=1e-12)
+
+
 def test_status_codes():
     adj = [[1, 2, 3], [0], [0], [0]]
     indptr, indices = csr_from_adj(adj)
