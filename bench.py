@@ -284,6 +284,32 @@ def main():
                     "achieved": agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else 0.0, "unit": "GB/s",
                     "frac": agg_bytes / (agg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if agg_ms > 0 else 0.0}
         del agg_out
+        # the same block through one whole GraphSAGE layer on the matrix cores (half in, 256 half out)
+        if feat.dtype == torch.float16 and w.feat_dim % 8 == 0 and w.feat_dim <= 256:
+            hid = 256
+            lw = smfg.sage_pack_weights((torch.randn((hid, 2 * w.feat_dim), device=dev) / w.feat_dim ** 0.5)
+                                        .to(torch.float16))
+            lb = torch.zeros(hid, dtype=torch.float32, device=dev)
+            lay_out = torch.empty((outs[q][0].indptr[L - 1].numel() - 1, hid), dtype=torch.float16, device=dev)
+            smfg.profile_begin(2, 4 * G)
+            lay_bytes = lay_flops = 0
+            for rep in range(2):
+                for b in range(k_set):
+                    o, c = outs[q][b], cnt[c0 + b]
+                    n_dst, e_last = c[L - 1], c[2 * L]
+                    cview = counts_all[W + c0 + b]
+                    smfg.sage_layer(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.indptr[L - 1].numel() - 1,
+                                    o.features, lw, lb, True, lay_out, stream=streams[0])
+                    lay_bytes += (e_last + n_dst) * row_bytes + 4 * e_last + 4 * (n_dst + 1) + 2 * hid * n_dst
+                    lay_flops += 2 * n_dst * 2 * w.feat_dim * hid
+            torch.cuda.synchronize()
+            lay_ms, lay_n = smfg.profile_end()["sage_layer"]
+            consumer["layer"] = {"kernel": "k_sage_layer", "block": f"hop {L - 1}", "out_dim": hid, "launches": lay_n,
+                                 "avg_launch_ms": lay_ms / max(1, lay_n),
+                                 "achieved": lay_bytes / (lay_ms * 1e-3) / 1e9 if lay_ms > 0 else 0.0, "unit": "GB/s",
+                                 "frac": lay_bytes / (lay_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if lay_ms > 0 else 0.0,
+                                 "TFLOPs": lay_flops / (lay_ms * 1e-3) / 1e12 if lay_ms > 0 else 0.0}
+            del lay_out, lw, lb
 
     result = {
         "metric": "sampled mini-batches/sec (MFG build + feature gather)",

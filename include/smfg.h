@@ -219,6 +219,38 @@ int smfg_mean_aggregate(const int32_t *d_indptr, const int32_t *d_indices, int64
                         const int64_t *d_num_dst, int64_t max_dst, const void *d_x, int64_t max_src,
                         int32_t dim, int32_t elem_bytes, float *d_out, void *hip_stream);
 
+/*
+ * One whole GraphSAGE layer over a block, with the aggregation fused into the linear transform
+ * (equation 1 with the choices section 2.1 names for GraphSAGE: agg = mean, upd = a linear layer
+ * on the concatenation of the node's own representation and the mean; ReLU between layers as in
+ * the model listing of Appendix C):
+ *   out[i, j] = act(bias[j] + sum_c w[j, c] x[i, c] + sum_c w[j, dim + c] mean_i[c]),  i < *d_num_dst,
+ * mean_i as in smfg_mean_aggregate, act = max(., 0) if relu != 0 else the identity.
+ *   d_x     device, IEEE half, row-major [max_src x dim], dense, 16-byte aligned; dim a multiple of
+ *           8, at most 256.  Destination i is source i, so row i is also the node's own row
+ *           (destinations beyond max_src are not computed).
+ *   w       IEEE half, row-major [out_dim x 2 dim] (a linear layer's weight: columns [0, dim)
+ *           act on the own row, [dim, 2 dim) on the mean); out_dim >= 1.  The layer call takes
+ *           it re-arranged for the matrix cores: smfg_sage_pack_weights writes that arrangement
+ *           (smfg_sage_packed_bytes bytes, 0 for unsupported sizes; both buffers device, 16-byte
+ *           aligned; asynchronous) once per set of weights.
+ *   d_bias  device, float [out_dim], or NULL.
+ *   d_out   device, row-major [max_dst x out_dim] of out_elem_bytes 2 (half, round to nearest) or
+ *           4 (float).
+ * Arithmetic: the mean is summed in float in slot order, divided once and rounded to half; the
+ * products of halfs are exact and are added in float on the matrix cores in an unspecified order.
+ * With S = |bias[j]| + sum_c |w||x| + sum_c |w| mean|x| the error of an output is at most
+ * S * (2^-11 + (2 dim + k_i + 2) * 2^-24), plus half an ulp of the half result if out is half.
+ * Offsets and source ids are clamped as in smfg_mean_aggregate.  Asynchronous on hip_stream.
+ */
+int64_t smfg_sage_packed_bytes(int32_t dim, int32_t out_dim);
+int smfg_sage_pack_weights(const void *d_w, int32_t dim, int32_t out_dim, void *d_packed,
+                           void *hip_stream);
+int smfg_sage_layer(const int32_t *d_indptr, const int32_t *d_indices, int64_t max_edges,
+                    const int64_t *d_num_dst, int64_t max_dst, const void *d_x, int64_t max_src,
+                    int32_t dim, const void *d_w_packed, const float *d_bias, int32_t out_dim, int32_t relu,
+                    void *d_out, int32_t out_elem_bytes, void *hip_stream);
+
 /* Copies counts[0 .. 2L+2) to the host after synchronising the stream; returns SMFG_OK or, if the
  * status word is non-zero, its (positive) SMFG_ST_* value. */
 int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, void *hip_stream);
@@ -238,7 +270,8 @@ int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, voi
 #define SMFG_STAGE_ASSEMBLE 5
 #define SMFG_STAGE_GATHER 6
 #define SMFG_STAGE_AGGREGATE 7
-#define SMFG_NUM_STAGES 8
+#define SMFG_STAGE_LAYER 8
+#define SMFG_NUM_STAGES 9
 int smfg_profile_begin(int32_t level, int32_t max_records);
 int smfg_profile_end(double *stage_ms /* host [SMFG_NUM_STAGES] */,
                      int64_t *stage_launches /* host [SMFG_NUM_STAGES] */);

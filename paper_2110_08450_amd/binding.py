@@ -31,10 +31,11 @@ EXPORTS = [
     "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_validate", "smfg_graph_set_labels", "smfg_bounds",
     "smfg_workspace_create", "smfg_workspace_create_sized",
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
-    "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
+    "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_sage_layer", "smfg_sage_pack_weights",
+    "smfg_sage_packed_bytes", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
 STAGES = ["clear", "seeds", "sample_insert", "flag_rows", "scan_tiles", "assemble", "gather",
-          "mean_aggregate"]
+          "mean_aggregate", "sage_layer"]
 
 
 class SmfgError(RuntimeError):
@@ -84,13 +85,17 @@ def lib() -> ctypes.CDLL:
         L.smfg_gather_rows.argtypes = [vp, vp, vp, i64, vp, vp]
         L.smfg_gather_many.argtypes = [vp, ctypes.POINTER(_Output), i32, i32, vp]
         L.smfg_mean_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, i32, i32, vp, vp]
+        L.smfg_sage_layer.argtypes = [vp, vp, i64, vp, i64, vp, i64, i32, vp, vp, i32, i32, vp, i32, vp]
+        L.smfg_sage_packed_bytes.argtypes = [i32, i32]
+        L.smfg_sage_packed_bytes.restype = i64
+        L.smfg_sage_pack_weights.argtypes = [vp, i32, i32, vp, vp]
         L.smfg_read_counts.argtypes = [ctypes.POINTER(_Output), i32, ctypes.POINTER(i64), vp]
         L.smfg_profile_begin.argtypes = [i32, i32]
         L.smfg_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         L.smfg_strerror.argtypes = [ctypes.c_int]
         L.smfg_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
-            if name != "smfg_workspace_bytes" and name != "smfg_strerror":
+            if name not in ("smfg_workspace_bytes", "smfg_strerror", "smfg_sage_packed_bytes"):
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -328,6 +333,46 @@ def mean_aggregate(indptr: torch.Tensor, indices: torch.Tensor, num_dst: torch.T
                                    ctypes.c_void_p(x.data_ptr()), x.shape[0], x.shape[1], x.element_size(),
                                    ctypes.c_void_p(out.data_ptr()), _stream_ptr(stream))
     _check(rc, "smfg_mean_aggregate")
+
+
+@dataclass
+class PackedWeights:
+    """A linear layer's weight [out_dim x 2 dim] re-arranged for smfg_sage_layer."""
+    data: torch.Tensor
+    dim: int
+    out_dim: int
+
+
+def sage_pack_weights(w: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> PackedWeights:
+    assert w.dim() == 2 and w.is_contiguous() and w.dtype == torch.float16 and w.shape[1] % 2 == 0
+    out_dim, dim = int(w.shape[0]), int(w.shape[1] // 2)
+    nbytes = int(lib().smfg_sage_packed_bytes(dim, out_dim))
+    if nbytes == 0:
+        raise SmfgError(ERR_INVALID_ARG, "smfg_sage_packed_bytes")
+    packed = torch.empty(nbytes // 2, dtype=torch.float16, device=w.device)
+    _check(lib().smfg_sage_pack_weights(ctypes.c_void_p(w.data_ptr()), dim, out_dim, ctypes.c_void_p(packed.data_ptr()),
+                                        _stream_ptr(stream)), "smfg_sage_pack_weights")
+    return PackedWeights(packed, dim, out_dim)
+
+
+def sage_layer(indptr: torch.Tensor, indices: torch.Tensor, num_dst: torch.Tensor, max_dst: int,
+               x: torch.Tensor, w: PackedWeights, bias: Optional[torch.Tensor], relu: bool, out: torch.Tensor,
+               stream: Optional[torch.cuda.Stream] = None) -> None:
+    """out[i] = act([x[i] | mean of x[indices[e]] over block row i] w^T + bias); x float16, w from
+    sage_pack_weights, bias float32 or None, out float16 or float32 [>= max_dst x out_dim]."""
+    assert indptr.dtype == torch.int32 and indices.dtype == torch.int32 and num_dst.dtype == torch.int64
+    assert x.dim() == 2 and x.is_contiguous() and x.dtype == torch.float16 and x.shape[1] == w.dim
+    assert bias is None or (bias.dtype == torch.float32 and bias.is_contiguous() and bias.numel() == w.out_dim)
+    assert out.dtype in (torch.float16, torch.float32) and out.is_contiguous() and out.shape[1] == w.out_dim
+    assert out.shape[0] >= max_dst and indptr.numel() >= max_dst + 1
+    rc = lib().smfg_sage_layer(ctypes.c_void_p(indptr.data_ptr()), ctypes.c_void_p(indices.data_ptr()),
+                               indices.numel(), ctypes.c_void_p(num_dst.data_ptr()), max_dst,
+                               ctypes.c_void_p(x.data_ptr()), x.shape[0], x.shape[1],
+                               ctypes.c_void_p(w.data.data_ptr()),
+                               ctypes.c_void_p(bias.data_ptr()) if bias is not None else None, w.out_dim,
+                               int(bool(relu)), ctypes.c_void_p(out.data_ptr()), out.element_size(),
+                               _stream_ptr(stream))
+    _check(rc, "smfg_sage_layer")
 
 
 def read_counts(out: Output, stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> List[int]:

@@ -675,6 +675,62 @@ int smfg_mean_aggregate(const int32_t* d_indptr, const int32_t* d_indices, int64
   return hip_err(hipGetLastError());
 }
 
+int64_t smfg_sage_packed_bytes(int32_t dim, int32_t out_dim) {
+  if (dim < 8 || dim % 8 != 0 || dim > kLayerMaxDim || out_dim < 1) return 0;
+  const int64_t slices = (static_cast<int64_t>(out_dim) + 31) / 32;
+  return slices * 32 * 2 * dim * static_cast<int64_t>(sizeof(_Float16));
+}
+
+int smfg_sage_pack_weights(const void* d_w, int32_t dim, int32_t out_dim, void* d_packed, void* hip_stream) {
+  if (!d_w || !d_packed) return SMFG_ERR_NULL_PTR;
+  const int64_t bytes = smfg_sage_packed_bytes(dim, out_dim);
+  if (bytes == 0) return SMFG_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(d_w) % 16 != 0 || reinterpret_cast<uintptr_t>(d_packed) % 16 != 0)
+    return SMFG_ERR_INVALID_ARG;
+  const int64_t vectors = bytes / 16;
+  k_sage_pack_weights<<<blocks_for(vectors, kThreads, 4096), kThreads, 0, static_cast<hipStream_t>(hip_stream)>>>(
+      static_cast<const _Float16*>(d_w), 2 * dim, out_dim, static_cast<half8_t*>(d_packed), vectors);
+  return hip_err(hipGetLastError());
+}
+
+int smfg_sage_layer(const int32_t* d_indptr, const int32_t* d_indices, int64_t max_edges, const int64_t* d_num_dst,
+                    int64_t max_dst, const void* d_x, int64_t max_src, int32_t dim, const void* d_w_packed,
+                    const float* d_bias, int32_t out_dim, int32_t relu, void* d_out, int32_t out_elem_bytes,
+                    void* hip_stream) {
+  if (!d_indptr || !d_indices || !d_num_dst || !d_x || !d_w_packed || !d_out) return SMFG_ERR_NULL_PTR;
+  if (dim < 8 || dim % 8 != 0 || dim > kLayerMaxDim || out_dim < 1 || (out_elem_bytes != 2 && out_elem_bytes != 4) ||
+      max_dst < 0 || max_dst >= (1ll << 31) || max_edges < 0 || max_edges >= (1ll << 31) || max_src < 1 ||
+      max_src >= (1ll << 31))
+    return SMFG_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(d_x) % 16 != 0 || reinterpret_cast<uintptr_t>(d_w_packed) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(d_out) % static_cast<uintptr_t>(out_elem_bytes) != 0)
+    return SMFG_ERR_INVALID_ARG;
+  if (max_dst == 0) return SMFG_OK;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const _Float16* x = static_cast<const _Float16*>(d_x);
+  const _Float16* w = static_cast<const _Float16*>(d_w_packed);
+  const int rows = dim <= 128 ? 64 : 32;
+  const unsigned gb = blocks_for(max_dst, rows, 0x7FFFFFFFu);
+  const size_t lds = static_cast<size_t>(rows) * static_cast<size_t>(2 * dim + kLayerPad) * sizeof(_Float16);
+  {
+    StageTimer t_(SMFG_STAGE_LAYER, st);
+    if (out_elem_bytes == 2) {
+      _Float16* o = static_cast<_Float16*>(d_out);
+      if (rows == 64)
+        k_sage_layer<_Float16, 64><<<gb, kThreads, lds, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, w, d_bias, out_dim, relu, o);
+      else
+        k_sage_layer<_Float16, 32><<<gb, kThreads, lds, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, w, d_bias, out_dim, relu, o);
+    } else {
+      float* o = static_cast<float*>(d_out);
+      if (rows == 64)
+        k_sage_layer<float, 64><<<gb, kThreads, lds, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, w, d_bias, out_dim, relu, o);
+      else
+        k_sage_layer<float, 32><<<gb, kThreads, lds, st>>>(d_indptr, d_indices, max_edges, d_num_dst, max_dst, x, max_src, dim, w, d_bias, out_dim, relu, o);
+    }
+  }
+  return hip_err(hipGetLastError());
+}
+
 int smfg_read_counts(const smfg_output_t* out, int32_t L, int64_t* h_counts, void* hip_stream) {
   if (!out || !out->counts || !h_counts) return SMFG_ERR_NULL_PTR;
   if (L < 1 || L > SMFG_MAX_LAYERS) return SMFG_ERR_TOO_MANY_LAYERS;

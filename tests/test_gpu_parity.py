@@ -712,3 +712,62 @@ def test_mean_aggregate_long_and_empty_rows(fanouts):
     assert np.isnan(y[n_dst:].cpu().numpy()).all()
     assert (np.abs(got - mean) <= np.maximum(k, 1)[:, None] * 2.0 ** -24 * mag).all()
     assert (got[k == 0] == 0).all()
+
+
+@pytest.mark.parametrize("dim,out_dims,out_dtype,with_bias", [
+    (128, (256, 256, 64), torch.float16, True),      # the shape of the papers workload, 64-row tiles
+    (64, (48, 40, 1), torch.float32, False),         # output widths that are no multiple of 32
+    (256, (128, 8, 100), torch.float16, True),       # 32-row tiles
+    (8, (16, 24, 5), torch.float32, True),           # smallest input width
+])
+def test_sage_layer_consumer(dim, out_dims, out_dtype, with_bias):
+    """Three GraphSAGE layers over the blocks of a sampled batch, outermost hop first, ReLU after all
+    but the last (model listing of Appendix C), each compared with the fp64 oracle fed the same
+    half inputs.  Bound per output: S (2^-11 + (2 dim + k + 2) 2^-24) for the half rounding of the
+    mean and the float sums, plus the rounding of a half result; S = sum of |w| |input| + |bias|."""
+    rng = np.random.default_rng(dim + out_dims[0])
+    adj = random_simple_graph(4000, 14, rng, hub=700)
+    adj[3] = []
+    adj = [[u for u in row if u != 3] for row in adj]
+    indptr, indices = csr_from_adj(adj)
+    feat = (rng.standard_normal((4000, dim)) * 2).astype(np.float16)
+    gg = GpuGraph(indptr, indices, feat)
+    seeds = np.concatenate([[3], rng.choice(np.arange(4, 4000), size=700, replace=False)]).astype(np.int32)
+    fan = (7, 5, 3)
+    ws = smfg.workspace_create(gg.g, len(seeds), fan)
+    out = smfg.alloc_output(gg.g, len(seeds), fan)
+    smfg.sample_mfg(gg.g, ws, torch.from_numpy(seeds).to(DEV), fan, 31, out)
+    res = fetch(out, 3)
+    ref = gg.oracle.sample_mfg(seeds, fan, 31)
+    assert_same(res, ref, 3)
+    x_gpu = out.features
+    x_ref = ref.features.view(np.float16).reshape(-1, dim)
+    d_in = dim
+    for layer, h in enumerate((2, 1, 0)):
+        d_out = out_dims[layer]
+        relu = layer < 2
+        w = (rng.standard_normal((d_out, 2 * d_in)) / np.sqrt(d_in)).astype(np.float16)
+        b = (rng.standard_normal(d_out) * 0.5).astype(np.float32) if with_bias else None
+        n_dst = res["n"][h]
+        y = torch.full((out.node_capacity, d_out), float("nan"), dtype=out_dtype, device=DEV)
+        smfg.sage_layer(out.indptr[h], out.indices[h], out.counts[h:h + 1], out.indptr[h].numel() - 1, x_gpu,
+                        smfg.sage_pack_weights(torch.from_numpy(w).to(DEV)),
+                        torch.from_numpy(b).to(DEV) if b is not None else None, relu, y)
+        torch.cuda.synchronize()
+        want, mag = oracle.sage_layer(ref.indptr[h], ref.indices[h], np.ascontiguousarray(x_ref),
+                                      w.astype(np.float64), None if b is None else b.astype(np.float64), relu)
+        got = y[:n_dst].float().cpu().numpy().astype(np.float64)
+        assert np.isnan(y[n_dst:].float().cpu().numpy()).all()         # nothing written past n_dst
+        k = np.diff(ref.indptr[h]).astype(np.float64)
+        tol = mag * (2.0 ** -11 + (2 * d_in + k[:, None] + 2) * 2.0 ** -24)
+        if out_dtype == torch.float16:
+            tol = tol + np.abs(want) * 2.0 ** -11 + 2.0 ** -24
+        assert (np.abs(got - want) <= tol).all(), f"layer {layer}: worst {np.max(np.abs(got - want) / tol)}"
+        if relu:
+            assert (got >= 0).all() and (got == 0).any() and (got > 0).any()
+        # the next layer continues from the GPU's output as halfs on both sides
+        x_gpu = y[:n_dst].to(torch.float16).contiguous()
+        x_ref = x_gpu.cpu().numpy()
+        d_in = d_out if d_out % 8 == 0 and d_out >= 8 else None
+        if d_in is None:
+            break
