@@ -765,6 +765,13 @@ def test_sage_layer_consumer(dim, out_dims, out_dtype, with_bias):
         assert (np.abs(got - want) <= tol).all(), f"layer {layer}: worst {np.max(np.abs(got - want) / tol)}"
         if relu:
             assert (got >= 0).all() and (got == 0).any() and (got > 0).any()
+        if layer == 0 and d_out > 1:
+            # the bound is tight enough to tell a wrong layer: an oracle with the two halves of W
+            # exchanged (a mistake planted on the CPU side) is far outside it
+            w_bad = np.concatenate([w[:, d_in:], w[:, :d_in]], axis=1).astype(np.float64)
+            bad, _ = oracle.sage_layer(ref.indptr[h], ref.indices[h], np.ascontiguousarray(x_ref), w_bad,
+                                       None if b is None else b.astype(np.float64), relu)
+            assert (np.abs(got - bad) > 10 * tol).mean() > 0.25
         # the next layer continues from the GPU's output as halfs on both sides
         x_gpu = y[:n_dst].to(torch.float16).contiguous()
         x_ref = x_gpu.cpu().numpy()
