@@ -242,21 +242,22 @@ __global__ void __launch_bounds__(kThreads, 4) k_sage_layer(const int32_t* __res
     for (int u = 0; u < kLayerAhead; ++u) bq[u] = wp[(u < nq ? u : 0) * 64];
     // one v_mfma_f32_32x32x16_f16 per vector: lane half hi supplies reduction indices 16 q + 8 hi .. + 8
     // of both operands (any assignment works as long as it is the same on both sides)
+    // The body is free of branches (a vector past the end multiplies zeros), so the LDS reads of
+    // the unrolled steps can be issued ahead of the MFMAs that use them.
     for (int qb = 0; qb < nq; qb += kLayerAhead) {
 #pragma unroll
       for (int u = 0; u < kLayerAhead; ++u) {
         const int q = qb + u;
-        const half8_t b = bq[u];
+        const half8_t zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        const half8_t b = q < nq ? bq[u] : zero;
         const int qn = q + kLayerAhead;
         bq[u] = wp[(qn < nq ? qn : 0) * 64];
-        if (q < nq) {
-          const int k0 = q * 16;
-          const half8_t a0 = *reinterpret_cast<const half8_t*>(ap0 + k0);
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b, acc0, 0, 0, 0);
-          if constexpr (ROWS == 64) {
-            const half8_t a1 = *reinterpret_cast<const half8_t*>(ap1 + k0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b, acc1, 0, 0, 0);
-          }
+        const int k0 = (q < nq ? q : 0) * 16;
+        const half8_t a0 = *reinterpret_cast<const half8_t*>(ap0 + k0);
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b, acc0, 0, 0, 0);
+        if constexpr (ROWS == 64) {
+          const half8_t a1 = *reinterpret_cast<const half8_t*>(ap1 + k0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b, acc1, 0, 0, 0);
         }
       }
     }
