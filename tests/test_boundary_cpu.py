@@ -38,6 +38,16 @@ def test_bounds_and_host_validation():
     assert "duplicate" in smfg.strerror(smfg.ST_DUPLICATE_SEED)
 
 
+def test_packed_weight_size_is_host_only():
+    """smfg_sage_packed_bytes: whole 32-column slices of halfs; 0 for widths the layer does not take."""
+    L = smfg.lib()
+    assert L.smfg_sage_packed_bytes(128, 256) == 256 * 256 * 2
+    assert L.smfg_sage_packed_bytes(8, 1) == 32 * 16 * 2
+    assert L.smfg_sage_packed_bytes(256, 33) == 64 * 512 * 2
+    for dim, out_dim in [(0, 8), (12, 8), (264, 8), (128, 0), (-8, 8)]:
+        assert L.smfg_sage_packed_bytes(dim, out_dim) == 0
+
+
 def test_oracle_and_library_agree_on_bounds():
     import oracle
     for seeds, fan, n in [(256, (10, 5), 10_000), (4096, (20, 20, 20), 111_000_000), (5, (32,), 20),

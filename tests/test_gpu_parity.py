@@ -778,3 +778,33 @@ def test_sage_layer_consumer(dim, out_dims, out_dtype, with_bias):
         d_in = d_out if d_out % 8 == 0 and d_out >= 8 else None
         if d_in is None:
             break
+
+
+def test_sage_layer_argument_errors_and_empty_block():
+    x = torch.zeros((16, 16), dtype=torch.float16, device=DEV)
+    indptr = torch.zeros(17, dtype=torch.int32, device=DEV)
+    indices = torch.zeros(4, dtype=torch.int32, device=DEV)
+    one = torch.tensor([16], dtype=torch.int64, device=DEV)
+    wp = smfg.sage_pack_weights(torch.ones((8, 32), dtype=torch.float16, device=DEV))
+    out = torch.full((16, 8), float("nan"), dtype=torch.float32, device=DEV)
+    with pytest.raises(smfg.SmfgError) as ei:                      # a width that is no multiple of 8
+        smfg.sage_pack_weights(torch.ones((8, 24), dtype=torch.float16, device=DEV))
+    assert ei.value.code == smfg.ERR_INVALID_ARG
+    L = smfg.lib()
+    import ctypes
+    vp = ctypes.c_void_p
+    args = lambda dim, out_eb: (vp(indptr.data_ptr()), vp(indices.data_ptr()), 4, vp(one.data_ptr()), 16, vp(x.data_ptr()),
+                                16, dim, vp(wp.data.data_ptr()), None, 8, 0, vp(out.data_ptr()), out_eb, None)
+    assert L.smfg_sage_layer(*args(12, 4)) == smfg.ERR_INVALID_ARG
+    assert L.smfg_sage_layer(*args(16, 3)) == smfg.ERR_INVALID_ARG
+    assert L.smfg_sage_layer(*((None,) + args(16, 4)[1:])) == smfg.ERR_NULL_PTR
+    # all destinations empty: the output is the own-row half of the product, the mean half is zero
+    x.copy_(torch.arange(16, device=DEV).view(16, 1).expand(16, 16).to(torch.float16))
+    smfg.sage_layer(indptr, indices, one, 16, x, wp, None, False, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, (torch.arange(16, device=DEV).float() * 16).view(16, 1).expand(16, 8))
+    # zero destinations: nothing is written
+    out.fill_(float("nan"))
+    smfg.sage_layer(indptr, indices, torch.zeros(1, dtype=torch.int64, device=DEV), 16, x, wp, None, False, out)
+    torch.cuda.synchronize()
+    assert torch.isnan(out).all()
