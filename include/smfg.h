@@ -70,6 +70,8 @@ extern "C" {
 #define SMFG_ST_TABLE_FULL 3        /* dedup table exhausted (only if node capacity is too) */
 #define SMFG_ST_SEED_OUT_OF_RANGE 4 /* a seed is < 0 or >= num_nodes */
 #define SMFG_ST_DUPLICATE_SEED 5    /* the seed list holds a node twice */
+#define SMFG_ST_INTERNAL 6          /* a kernel met a state its own invariants exclude (a defect, or
+                                       scratch memory overwritten from outside during the call) */
 
 typedef struct smfg_graph smfg_graph_t;         /* opaque; BORROWS the device arrays given to it */
 typedef struct smfg_workspace smfg_workspace_t; /* opaque; OWNS the scratch of one in-flight batch */
@@ -80,6 +82,8 @@ typedef struct smfg_workspace smfg_workspace_t; /* opaque; OWNS the scratch of o
  * duplicates (else "without replacement" holds for positions, not neighbours).
  *   d_indptr   device, int64 [num_nodes + 1], non-decreasing, d_indptr[0] = 0; each degree < 2^31
  *   d_indices  device, int32 [num_edges], values in [0, num_nodes)
+ *              (both naturally aligned, like every typed pointer of this interface: a pointer that
+ *              is not a multiple of its element size is refused with SMFG_ERR_INVALID_ARG)
  *   d_feat     device, row-major, row v at byte offset v * row_stride_bytes, the first
  *              feat_dim * elem_bytes bytes of a row are its features (any elem_bytes >= 1;
  *              rows are moved as opaque bytes, no conversion).  May be NULL: no gather then.
@@ -256,7 +260,9 @@ int smfg_sage_layer(const int32_t *d_indptr, const int32_t *d_indices, int64_t m
 int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, void *hip_stream);
 
 /*
- * Stage timing for measurement (not thread safe; one profile at a time per process).
+ * Stage timing for measurement.  One profile at a time per process; begin and end must not run
+ * while another thread is inside any other call of this library (the record list is process-wide
+ * state that the sampling calls append to).
  * Between begin and end, launches are bracketed by HIP events on the call's own stream:
  * level 1 = only the feature gather launch, level 2 = every launch.  At most max_records
  * launches are recorded, later ones run untimed.  smfg_profile_end synchronises the device,

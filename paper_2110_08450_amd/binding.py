@@ -24,6 +24,7 @@ OK = 0
 ERR_INVALID_ARG, ERR_NULL_PTR, ERR_BAD_FANOUT, ERR_TOO_MANY_LAYERS = -1, -2, -3, -4
 ERR_TOO_MANY_SEEDS, ERR_OOM, ERR_CAPACITY, ERR_BAD_GRAPH, ERR_HIP_BASE = -5, -6, -7, -8, -1000
 ST_NODE_CAPACITY, ST_EDGE_CAPACITY, ST_TABLE_FULL, ST_SEED_OUT_OF_RANGE, ST_DUPLICATE_SEED = 1, 2, 3, 4, 5
+ST_INTERNAL = 6
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsmfg.so")
 

@@ -51,7 +51,9 @@ __global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
 // floor(64 / d) groups (its last 64 mod d lanes idle).
 __global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
   const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  // other blocks of this launch may set the status at any time: leave as whole waves only, the
+  // lanes below talk to each other
+  if (__any(status_of(B, P.L) != 0)) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const int d = P.d;
   const int lane = threadIdx.x & 63;
@@ -308,8 +310,15 @@ __global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
               local = static_cast<uint32_t>(n) + t + m.y + __popc(m.x & ((1u << qs) - 1u));
               break;
             }
-            const uint32_t nxt = B.ent[qq] & ~kTagMask;  // strictly smaller position
-            if (nxt >= qq) break;                        // cannot happen; guards the loop
+            // Positions strictly decrease along a chain (a sample only ever points at an earlier
+            // one), so the walk ends at a first appearance; anything else means the scratch arrays
+            // were disturbed, which is reported rather than turned into a wrong index.
+            const uint32_t nxt = B.ent[qq] & ~kTagMask;
+            if (nxt >= qq) {
+              set_status(B, P.L, SMFG_ST_INTERNAL);
+              local = 0u;
+              break;
+            }
             qq = nxt;
             qqi = qq / d;
             m = B.rowmn[qqi];

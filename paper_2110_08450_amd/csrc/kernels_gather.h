@@ -58,7 +58,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <typename V>
 __global__ void __launch_bounds__(kThreads) k_gather(const Launch P) {
   const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  if (B.features == nullptr || status_of(B, P.L) != 0) return;
   int64_t n = B.counts[P.L];
   if (n > B.node_capacity) n = B.node_capacity;
   gather_rows<V>(P.feat, P.row_stride, static_cast<uint32_t>(P.row_bytes / sizeof(V)), P.num_nodes,

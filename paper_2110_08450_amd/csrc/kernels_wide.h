@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
 __global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P) {
   __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
   const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  if (__any(status_of(B, P.L) != 0)) return;  // whole waves only: the lanes below cooperate
   const int n = static_cast<int>(B.counts[P.h]);
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -222,8 +222,12 @@ __global__ void __launch_bounds__(kThreads) k_assemble_flat(const Launch P) {
             local = n + static_cast<uint32_t>(B.stile_sums[q / kWideTile]) + B.rank[q];
             break;
           }
-          const uint32_t nxt = eq & ~kTagMask;  // strictly smaller position
-          if (nxt >= q) break;                  // cannot happen; guards the loop
+          const uint32_t nxt = eq & ~kTagMask;  // strictly smaller position, or the scratch was disturbed
+          if (nxt >= q) {
+            set_status(B, P.L, SMFG_ST_INTERNAL);
+            local = 0u;
+            break;
+          }
           q = nxt;
         }
       }

@@ -33,6 +33,7 @@
 // atomic minimum, so the surviving value is the smallest position whatever the schedule.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -70,7 +71,7 @@ inline int vec_bytes(uintptr_t a, uintptr_t b, int64_t row_bytes, int64_t row_st
 struct Profiler {
   int level = 0;
   int max_records = 0;
-  int used = 0;
+  std::atomic<int> used{0};  // launches may be issued from several threads while a profile is open
   hipEvent_t* ev = nullptr;  // 2 per record
   int* stage = nullptr;
 } g_prof;
@@ -81,8 +82,9 @@ struct StageTimer {
   StageTimer(int stage, hipStream_t s) : st(s) {
     if (g_prof.level == 0) return;
     if (g_prof.level == 1 && stage != SMFG_STAGE_GATHER) return;
-    if (g_prof.used >= g_prof.max_records) return;
-    rec = g_prof.used++;
+    const int r = g_prof.used.fetch_add(1, std::memory_order_relaxed);
+    if (r >= g_prof.max_records) return;
+    rec = r;
     g_prof.stage[rec] = stage;
     (void)hipEventRecord(g_prof.ev[2 * rec], st);
   }
@@ -96,8 +98,16 @@ void profiler_free() {
     if (g_prof.ev && g_prof.ev[i]) (void)hipEventDestroy(g_prof.ev[i]);
   std::free(g_prof.ev);
   std::free(g_prof.stage);
-  g_prof = Profiler();
+  g_prof.level = 0;
+  g_prof.max_records = 0;
+  g_prof.used.store(0);
+  g_prof.ev = nullptr;
+  g_prof.stage = nullptr;
 }
+
+// Typed device pointers must be multiples of their element size (atomics and vector accesses on a
+// misaligned address are undefined).
+inline bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 inline unsigned blocks_for(int64_t work_items, int64_t per_block, unsigned cap) {
   int64_t b = (work_items + per_block - 1) / per_block;
@@ -124,8 +134,9 @@ struct smfg_workspace {
   int32_t max_seeds, L;
   int32_t fanouts[SMFG_MAX_LAYERS];
   int64_t node_capacity;
-  int64_t slot_entries;  // capacity of `slot`
+  int64_t slot_entries;  // capacity of the per-sample arrays
   int64_t bytes;
+  int64_t b_table, b_slot, b_row, b_tiles, b_stiles;  // byte sizes of the parts of the slab
   uint32_t table_log2;
   void* slab;
   uint64_t* table;
@@ -174,6 +185,62 @@ int check_fanouts(int32_t L, const int32_t* fanouts, bool* wide = nullptr) {
   return SMFG_OK;
 }
 
+inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
+
+// Sizes of a workspace for up to max_seeds seeds, the given fanouts and capacities: fills every
+// field of *ws but the pointers (slab stays null).  Host only.
+int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, int32_t L, const int32_t* fanouts,
+                   int64_t node_capacity, int64_t sample_capacity) {
+  std::memset(ws, 0, sizeof(*ws));
+  int rc = check_fanouts(L, fanouts);
+  if (rc != SMFG_OK) return rc;
+  if (max_seeds < 0 || node_capacity < 0 || sample_capacity < 0) return SMFG_ERR_INVALID_ARG;
+  int64_t mn[SMFG_MAX_LAYERS + 1], me[SMFG_MAX_LAYERS];
+  smfg_bounds(max_seeds, L, fanouts, g->num_nodes, mn, me);
+  if (node_capacity == 0 || node_capacity > mn[L]) node_capacity = mn[L];
+  if (node_capacity < 1) node_capacity = 1;
+  if (node_capacity < mn[0]) return SMFG_ERR_TOO_MANY_SEEDS;
+  int64_t slots = slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity);
+  if (sample_capacity > 0) slots = sample_capacity;
+  if (slots < 0) return SMFG_ERR_INVALID_ARG;  // SMFG_FANOUT_ALL needs an explicit sample capacity
+  if (slots >= (1ll << 30) || node_capacity > (1ll << 29)) return SMFG_ERR_CAPACITY;
+  uint32_t lg = 10;
+  while ((1ll << lg) < 2 * node_capacity) ++lg;
+  ws->device = g->device;
+  ws->max_seeds = max_seeds;
+  ws->L = L;
+  for (int h = 0; h < L; ++h) ws->fanouts[h] = fanouts[h];
+  ws->node_capacity = node_capacity;
+  ws->slot_entries = slots > 0 ? slots : 1;
+  ws->table_log2 = lg;
+  const int64_t tiles = (node_capacity + kTileRows - 1) / kTileRows + 1;
+  ws->b_table = align256((int64_t(1) << lg) * 8);
+  ws->b_slot = align256(ws->slot_entries * 4);
+  ws->b_row = align256((node_capacity + 4) * 4);
+  ws->b_tiles = align256(tiles * 8);
+  ws->b_stiles = align256((ws->slot_entries / kWideTile + 2) * 8);
+  ws->bytes = ws->b_table + 4 * ws->b_slot + 8 * ws->b_row + ws->b_tiles + ws->b_stiles;
+  return SMFG_OK;
+}
+
+// Points the arrays of a planned workspace into `base` (ws->bytes bytes, 256-byte aligned).
+void bind_workspace(smfg_workspace* ws, void* base) {
+  uint8_t* p = static_cast<uint8_t*>(base);
+  ws->table = reinterpret_cast<uint64_t*>(p); p += ws->b_table;
+  ws->ent = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
+  ws->lostto = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
+  ws->gsrc = reinterpret_cast<int32_t*>(p); p += ws->b_slot;
+  ws->rank = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
+  ws->rowk = reinterpret_cast<int32_t*>(p); p += ws->b_row;
+  ws->rowmn = reinterpret_cast<uint2*>(p); p += 2 * ws->b_row;
+  ws->rowoff = reinterpret_cast<int32_t*>(p); p += ws->b_row;
+  ws->rowstart = reinterpret_cast<int64_t*>(p); p += 2 * ws->b_row;
+  ws->rowdeg = reinterpret_cast<int32_t*>(p); p += ws->b_row;
+  p += ws->b_row;  // spare
+  ws->tile_sums = reinterpret_cast<uint64_t*>(p); p += ws->b_tiles;
+  ws->stile_sums = reinterpret_cast<uint64_t*>(p);
+}
+
 // The gather launch shared by smfg_sample_mfg_many and smfg_gather_many.
 void launch_gather(const Launch& P, int64_t max_rows, int vb, unsigned G, hipStream_t st) {
   const unsigned gb = blocks_for(max_rows, kGatherRows, 0x7FFFFFFFu);
@@ -198,6 +265,7 @@ int smfg_graph_create(smfg_graph_t** out, int64_t num_nodes, int64_t num_edges, 
   *out = nullptr;
   if (!d_indptr || (num_edges > 0 && !d_indices)) return SMFG_ERR_NULL_PTR;
   if (num_nodes < 0 || num_nodes >= (1ll << 31) || num_edges < 0) return SMFG_ERR_INVALID_ARG;
+  if (misaligned(d_indptr, 8) || misaligned(d_indices, 4)) return SMFG_ERR_INVALID_ARG;
   int64_t row_bytes = 0;
   if (d_feat) {
     if (feat_dim < 1 || elem_bytes < 1) return SMFG_ERR_INVALID_ARG;
@@ -307,43 +375,13 @@ int smfg_workspace_create_sized(smfg_workspace_t** out, const smfg_graph_t* g, i
   if (!out) return SMFG_ERR_NULL_PTR;
   *out = nullptr;
   if (!g) return SMFG_ERR_NULL_PTR;
-  int rc = check_fanouts(L, fanouts);
-  if (rc != SMFG_OK) return rc;
-  if (max_seeds < 0 || node_capacity < 0 || sample_capacity < 0) return SMFG_ERR_INVALID_ARG;
-  int64_t mn[SMFG_MAX_LAYERS + 1], me[SMFG_MAX_LAYERS];
-  smfg_bounds(max_seeds, L, fanouts, g->num_nodes, mn, me);
-  if (node_capacity == 0 || node_capacity > mn[L]) node_capacity = mn[L];
-  if (node_capacity < 1) node_capacity = 1;
-  if (node_capacity < mn[0]) return SMFG_ERR_TOO_MANY_SEEDS;
-  int64_t slots = slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity);
-  if (sample_capacity > 0) slots = sample_capacity;
-  if (slots < 0) return SMFG_ERR_INVALID_ARG;  // SMFG_FANOUT_ALL needs an explicit sample capacity
-  if (slots >= (1ll << 30) || node_capacity > (1ll << 29)) return SMFG_ERR_CAPACITY;
-
-  uint32_t lg = 10;
-  while ((1ll << lg) < 2 * node_capacity) ++lg;
-
   smfg_workspace* ws = new (std::nothrow) smfg_workspace;
   if (!ws) return SMFG_ERR_OOM;
-  std::memset(ws, 0, sizeof(*ws));
-  ws->device = g->device;
-  ws->max_seeds = max_seeds;
-  ws->L = L;
-  for (int h = 0; h < L; ++h) ws->fanouts[h] = fanouts[h];
-  ws->node_capacity = node_capacity;
-  ws->slot_entries = slots > 0 ? slots : 1;
-  ws->table_log2 = lg;
-
-  auto align = [](int64_t x) { return (x + 255) & ~int64_t(255); };
-  const int64_t tiles = (node_capacity + kTileRows - 1) / kTileRows + 1;
-  const int64_t b_table = align((int64_t(1) << lg) * 8);
-  const int64_t b_slot = align(ws->slot_entries * 4);
-  const int64_t b_rowk = align((node_capacity + 4) * 4);
-  const int64_t b_mask = align((node_capacity + 4) * 4);
-  const int64_t b_tiles = align(tiles * 8);
-  const int64_t b_start = align((node_capacity + 4) * 8);
-  const int64_t b_stiles = align((ws->slot_entries / kWideTile + 2) * 8);
-  ws->bytes = b_table + 4 * b_slot + 5 * b_rowk + b_tiles + b_start + b_stiles;
+  int rc = plan_workspace(ws, g, max_seeds, L, fanouts, node_capacity, sample_capacity);
+  if (rc != SMFG_OK) {
+    delete ws;
+    return rc;
+  }
   int cur = 0;
   (void)hipGetDevice(&cur);
   if (cur != g->device) (void)hipSetDevice(g->device);
@@ -354,21 +392,9 @@ int smfg_workspace_create_sized(smfg_workspace_t** out, const smfg_graph_t* g, i
     delete ws;
     return SMFG_ERR_OOM;
   }
-  uint8_t* p = static_cast<uint8_t*>(ws->slab);
-  ws->table = reinterpret_cast<uint64_t*>(p); p += b_table;
-  ws->ent = reinterpret_cast<uint32_t*>(p); p += b_slot;
-  ws->lostto = reinterpret_cast<uint32_t*>(p); p += b_slot;
-  ws->gsrc = reinterpret_cast<int32_t*>(p); p += b_slot;
-  ws->rowk = reinterpret_cast<int32_t*>(p); p += b_rowk;
-  ws->rowmn = reinterpret_cast<uint2*>(p); p += b_mask + b_rowk;
-  ws->rowoff = reinterpret_cast<int32_t*>(p); p += b_rowk;
-  ws->tile_sums = reinterpret_cast<uint64_t*>(p); p += b_tiles;
-  ws->rowstart = reinterpret_cast<int64_t*>(p); p += b_start;
-  ws->rowdeg = reinterpret_cast<int32_t*>(p); p += b_rowk;
-  ws->rank = reinterpret_cast<uint32_t*>(p); p += b_slot;
-  ws->stile_sums = reinterpret_cast<uint64_t*>(p);
+  bind_workspace(ws, ws->slab);
   // displacement notes start out clear; flag_rows clears whatever a call writes
-  e = hipMemset(ws->lostto, 0, static_cast<size_t>(b_slot));
+  e = hipMemset(ws->lostto, 0, static_cast<size_t>(ws->slot_entries) * 4);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (cur != g->device) (void)hipSetDevice(cur);
   if (e != hipSuccess) {
@@ -416,7 +442,8 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
   uint32_t max_table_log2 = 0;
   int32_t max_seeds = 0;
   int64_t max_entries = 0;
-  bool want_feat = false;
+  // either every batch gathers or none: the gather is one launch over all of them
+  const bool want_feat = g->feat && outs[0].features;
   int vb = 16;
 
   for (int b = 0; b < num_batches; ++b) {
@@ -429,8 +456,11 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     if (num_seeds[b] < 0) return SMFG_ERR_INVALID_ARG;
     if (num_seeds[b] > 0 && !d_seeds[b]) return SMFG_ERR_NULL_PTR;
     if (!o.node_ids || !o.counts) return SMFG_ERR_NULL_PTR;
+    if (misaligned(d_seeds[b], 4) || misaligned(o.node_ids, 4) || misaligned(o.counts, 8))
+      return SMFG_ERR_INVALID_ARG;
     for (int h = 0; h < L; ++h) {
       if (!o.indptr[h] || !o.indices[h]) return SMFG_ERR_NULL_PTR;
+      if (misaligned(o.indptr[h], 4) || misaligned(o.indices[h], 4)) return SMFG_ERR_INVALID_ARG;
       if (o.edge_capacity[h] < 0) return SMFG_ERR_INVALID_ARG;
     }
     if (o.node_capacity < 1) return SMFG_ERR_INVALID_ARG;
@@ -444,15 +474,12 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     if (!wide && slot_entries_needed(num_seeds[b], L, fanouts, g->num_nodes, ncap) > w->slot_entries)
       return SMFG_ERR_CAPACITY;
     if (w->slot_entries > max_entries) max_entries = w->slot_entries;
-    if (g->feat && o.features) {
-      want_feat = true;
+    if ((g->feat && o.features) != want_feat) return SMFG_ERR_INVALID_ARG;
+    if (want_feat) {
       const int v = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(o.features),
                               g->row_bytes, g->row_stride);
       if (v < vb) vb = v;
-    } else if (b > 0 && want_feat) {
-      return SMFG_ERR_INVALID_ARG;  // either every batch gathers or none
     }
-    if (b > 0 && !want_feat && g->feat && o.features) return SMFG_ERR_INVALID_ARG;
 
     BatchCtx& B = P.b[b];
     B.seeds = d_seeds[b];
@@ -596,6 +623,7 @@ int smfg_gather_many(const smfg_graph_t* g, const smfg_output_t* outs, int32_t n
   for (int b = 0; b < num_batches; ++b) {
     const smfg_output_t& o = outs[b];
     if (!o.node_ids || !o.counts || !o.features) return SMFG_ERR_NULL_PTR;
+    if (misaligned(o.node_ids, 4) || misaligned(o.counts, 8)) return SMFG_ERR_INVALID_ARG;
     if (o.node_capacity < 1 || o.node_capacity > (1ll << 29)) return SMFG_ERR_INVALID_ARG;
     const int v = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(o.features),
                             g->row_bytes, g->row_stride);
@@ -620,6 +648,7 @@ int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int
   if (!g || !d_node_ids || !d_num_rows || !d_out) return SMFG_ERR_NULL_PTR;
   if (!g->feat || g->num_nodes < 1) return SMFG_ERR_INVALID_ARG;
   if (max_rows < 0 || max_rows >= (1ll << 31)) return SMFG_ERR_INVALID_ARG;
+  if (misaligned(d_node_ids, 4) || misaligned(d_num_rows, 8)) return SMFG_ERR_INVALID_ARG;
   if (max_rows == 0) return SMFG_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int vb = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(d_out), g->row_bytes,
@@ -647,6 +676,9 @@ int smfg_mean_aggregate(const int32_t* d_indptr, const int32_t* d_indices, int64
   if (!d_indptr || !d_indices || !d_num_dst || !d_x || !d_out) return SMFG_ERR_NULL_PTR;
   if (dim < 1 || (elem_bytes != 2 && elem_bytes != 4) || max_dst < 0 || max_dst >= (1ll << 31) || max_edges < 0 ||
       max_edges >= (1ll << 31) || max_src < 1 || max_src >= (1ll << 31))
+    return SMFG_ERR_INVALID_ARG;
+  if (misaligned(d_indptr, 4) || misaligned(d_indices, 4) || misaligned(d_num_dst, 8) ||
+      misaligned(d_x, static_cast<uintptr_t>(elem_bytes)) || misaligned(d_out, 4))
     return SMFG_ERR_INVALID_ARG;
   if (max_dst == 0) return SMFG_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
@@ -705,6 +737,8 @@ int smfg_sage_layer(const int32_t* d_indptr, const int32_t* d_indices, int64_t m
   if (reinterpret_cast<uintptr_t>(d_x) % 16 != 0 || reinterpret_cast<uintptr_t>(d_w_packed) % 16 != 0 ||
       reinterpret_cast<uintptr_t>(d_out) % static_cast<uintptr_t>(out_elem_bytes) != 0)
     return SMFG_ERR_INVALID_ARG;
+  if (misaligned(d_indptr, 4) || misaligned(d_indices, 4) || misaligned(d_num_dst, 8) || misaligned(d_bias, 4))
+    return SMFG_ERR_INVALID_ARG;
   if (max_dst == 0) return SMFG_OK;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const _Float16* x = static_cast<const _Float16*>(d_x);
@@ -734,6 +768,7 @@ int smfg_sage_layer(const int32_t* d_indptr, const int32_t* d_indices, int64_t m
 int smfg_read_counts(const smfg_output_t* out, int32_t L, int64_t* h_counts, void* hip_stream) {
   if (!out || !out->counts || !h_counts) return SMFG_ERR_NULL_PTR;
   if (L < 1 || L > SMFG_MAX_LAYERS) return SMFG_ERR_TOO_MANY_LAYERS;
+  if (misaligned(out->counts, 8)) return SMFG_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipMemcpyAsync(h_counts, out->counts, sizeof(int64_t) * (2 * L + 2), hipMemcpyDeviceToHost, st);
   if (e != hipSuccess) return hip_err(e);
@@ -775,7 +810,8 @@ int smfg_profile_end(double* stage_ms, int64_t* stage_launches) {
     profiler_free();
     return hip_err(e);
   }
-  for (int r = 0; r < g_prof.used; ++r) {
+  const int used = g_prof.used.load() < g_prof.max_records ? g_prof.used.load() : g_prof.max_records;
+  for (int r = 0; r < used; ++r) {
     float ms = 0.f;
     e = hipEventElapsedTime(&ms, g_prof.ev[2 * r], g_prof.ev[2 * r + 1]);
     if (e != hipSuccess) {
@@ -805,6 +841,7 @@ const char* smfg_strerror(int code) {
     case SMFG_ST_TABLE_FULL: return "device: dedup table full";
     case SMFG_ST_SEED_OUT_OF_RANGE: return "device: seed out of range";
     case SMFG_ST_DUPLICATE_SEED: return "device: duplicate seed";
+    case SMFG_ST_INTERNAL: return "device: internal inconsistency (scratch memory disturbed during the call?)";
     default: return code <= SMFG_ERR_HIP_BASE ? "HIP runtime error" : "unknown code";
   }
 }

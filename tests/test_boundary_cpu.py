@@ -87,6 +87,36 @@ def test_output_struct_layout_matches_the_binding(tmp_path):
     assert smfg.MAX_LAYERS == 8 and smfg.MAX_BATCHES == 16 and smfg.MAX_FANOUT == 32
 
 
+def test_graph_create_refuses_bad_arguments_before_touching_a_device():
+    """Null, negative and misaligned arguments of smfg_graph_create are turned down by host checks
+    that come before the first HIP call, so they can be exercised without a GPU."""
+    L = smfg.lib()
+    h = ctypes.c_void_p()
+    vp = ctypes.c_void_p
+    ok_ptr = 0x7f0000001000      # never dereferenced: every case below is refused first
+    create = L.smfg_graph_create
+    assert create(None, 4, 8, vp(ok_ptr), vp(ok_ptr), None, 0, 0, 0) == smfg.ERR_NULL_PTR
+    assert create(ctypes.byref(h), 4, 8, None, vp(ok_ptr), None, 0, 0, 0) == smfg.ERR_NULL_PTR
+    assert create(ctypes.byref(h), 4, 8, vp(ok_ptr), None, None, 0, 0, 0) == smfg.ERR_NULL_PTR
+    assert create(ctypes.byref(h), -1, 8, vp(ok_ptr), vp(ok_ptr), None, 0, 0, 0) == smfg.ERR_INVALID_ARG
+    assert create(ctypes.byref(h), 1 << 31, 8, vp(ok_ptr), vp(ok_ptr), None, 0, 0, 0) == smfg.ERR_INVALID_ARG
+    assert create(ctypes.byref(h), 4, 8, vp(ok_ptr + 4), vp(ok_ptr), None, 0, 0, 0) == smfg.ERR_INVALID_ARG
+    assert create(ctypes.byref(h), 4, 8, vp(ok_ptr), vp(ok_ptr + 2), None, 0, 0, 0) == smfg.ERR_INVALID_ARG
+    assert create(ctypes.byref(h), 4, 8, vp(ok_ptr), vp(ok_ptr), vp(ok_ptr), 0, 2, 0) == smfg.ERR_INVALID_ARG
+    assert create(ctypes.byref(h), 4, 8, vp(ok_ptr), vp(ok_ptr), vp(ok_ptr), 8, 2, 15) == smfg.ERR_INVALID_ARG
+    assert h.value is None
+    # entry points that take raw arrays: null and misaligned pointers, before any launch
+    i64 = ctypes.c_int64
+    assert L.smfg_gather_rows(None, vp(ok_ptr), vp(ok_ptr), i64(4), vp(ok_ptr), None) == smfg.ERR_NULL_PTR
+    assert L.smfg_mean_aggregate(vp(ok_ptr + 2), vp(ok_ptr), i64(8), vp(ok_ptr), i64(4), vp(ok_ptr), i64(4), 8, 2,
+                                 vp(ok_ptr), None) == smfg.ERR_INVALID_ARG
+    assert L.smfg_mean_aggregate(vp(ok_ptr), vp(ok_ptr), i64(8), vp(ok_ptr + 4), i64(4), vp(ok_ptr), i64(4), 8, 2,
+                                 vp(ok_ptr), None) == smfg.ERR_INVALID_ARG
+    assert L.smfg_sage_layer(vp(ok_ptr), vp(ok_ptr + 1), i64(8), vp(ok_ptr), i64(4), vp(ok_ptr), i64(4), 8,
+                             vp(ok_ptr), None, 8, 0, vp(ok_ptr), 2, None) == smfg.ERR_INVALID_ARG
+    assert "internal" in smfg.strerror(smfg.ST_INTERNAL)
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys

@@ -254,6 +254,67 @@ def test_host_argument_errors(tiny):
     assert fetch(out, 1)["status"] == 0
 
 
+def test_host_argument_errors_of_a_launch_set(tiny):
+    """Mixed feature buffers, a label buffer without graph labels and misaligned pointers are
+    refused on the host before anything is launched (so these cases cannot touch the GPU)."""
+    import copy
+    import ctypes
+    w, gg, batches = tiny
+    fan = (10, 5)
+    seeds = [batches[b].to(DEV) for b in range(2)]
+    wss = [smfg.workspace_create(gg.g, 256, fan) for _ in range(2)]
+    outs = [smfg.alloc_output(gg.g, 256, fan) for _ in range(2)]
+
+    def variant(o, **fields):
+        v = copy.copy(o)
+        v.c = smfg._Output()
+        ctypes.memmove(ctypes.byref(v.c), ctypes.byref(o.c), ctypes.sizeof(smfg._Output))
+        for k, val in fields.items():
+            setattr(v.c, k, val)
+        return v
+
+    def code(fn):
+        with pytest.raises(smfg.SmfgError) as ei:
+            fn()
+        return ei.value.code
+
+    def many(os_, sd=seeds):
+        smfg.sample_mfg_many(gg.g, wss, sd, fan, [1, 2], os_)
+    # either every batch of a set gathers or none: both orders of the mix
+    assert code(lambda: many([variant(outs[0], features=None), outs[1]])) == smfg.ERR_INVALID_ARG
+    assert code(lambda: many([outs[0], variant(outs[1], features=None)])) == smfg.ERR_INVALID_ARG
+    # a label buffer needs the graph's label vector
+    lab = torch.zeros(256, dtype=torch.int64, device=DEV)
+    assert gg.g.labels is None
+    assert code(lambda: many([outs[0], variant(outs[1], labels=lab.data_ptr())])) == smfg.ERR_INVALID_ARG
+    # typed pointers must be multiples of their element size
+    room = torch.zeros(260, dtype=torch.int32, device=DEV)
+
+    class FakeSeeds:            # "256 int32" starting one byte off an int32 boundary
+        dtype = torch.int32
+
+        def numel(self):
+            return 256
+
+        def is_contiguous(self):
+            return True
+
+        def data_ptr(self):
+            return room.data_ptr() + 1
+    assert code(lambda: many(outs, [seeds[0], FakeSeeds()])) == smfg.ERR_INVALID_ARG
+    assert code(lambda: many([outs[0], variant(outs[1], counts=outs[1].counts.data_ptr() + 4)])) \
+        == smfg.ERR_INVALID_ARG
+    assert code(lambda: many([outs[0], variant(outs[1], node_ids=outs[1].node_ids.data_ptr() + 2)])) \
+        == smfg.ERR_INVALID_ARG
+    bad_blk = variant(outs[1])
+    bad_blk.c.indices[1] = outs[1].indices[1].data_ptr() + 1
+    assert code(lambda: many([outs[0], bad_blk])) == smfg.ERR_INVALID_ARG
+    # nothing above disturbed the handles: the plain call still matches the oracle
+    many(outs)
+    for b in range(2):
+        assert_same(fetch(outs[b], 2), gg.oracle.sample_mfg(batches[b].numpy(), fan, b + 1), 2)
+
+
 def test_mid_workload_sampled_batches():
     """arxiv-shaped workload: first, middle and the partial last batch, element by element."""
     w = synth.WORKLOADS["mid"]
