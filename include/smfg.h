@@ -177,6 +177,25 @@ int smfg_sample_mfg(const smfg_graph_t *g, smfg_workspace_t *ws, const int32_t *
                     const smfg_output_t *out, void *hip_stream);
 
 /*
+ * smfg_sample_mfg for callers that cannot allocate device memory or hold a workspace handle: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs and results as smfg_sample_mfg, but the scratch lives in a fixed array inside the
+ * library (SMFG_STATIC_SCRATCH_BYTES per GPU, held from the library's load until the process
+ * ends) and the call allocates and frees nothing.  The scratch needed grows with
+ * out->node_capacity and the fanouts exactly as smfg_workspace_bytes reports for a workspace
+ * created with (num_seeds, fanouts, out->node_capacity); a call that needs more than the array
+ * holds returns SMFG_ERR_CAPACITY and launches nothing (pass a smaller out->node_capacity - a
+ * batch that outgrows it ends with SMFG_ST_NODE_CAPACITY - or use a workspace).  Fanouts must be
+ * in [1, SMFG_MAX_WIDE_FANOUT] (SMFG_FANOUT_ALL has no size bound without a workspace:
+ * SMFG_ERR_INVALID_ARG).  All calls on one GPU share the array: two calls that overlap in time
+ * on the same GPU, on any streams, race; order them (one stream, or events).
+ */
+#define SMFG_STATIC_SCRATCH_BYTES (64u << 20)
+int smfg_sample_mfg_static(const smfg_graph_t *g, const int32_t *d_seeds, int32_t num_seeds,
+                           const int32_t *fanouts, int32_t L, uint64_t rng_key,
+                           const smfg_output_t *out, void *hip_stream);
+
+/*
  * The same for num_batches (1..SMFG_MAX_BATCHES) independent batches in one set of launches:
  * batch b uses ws[b], d_seeds[b], num_seeds[b], rng_keys[b], outs[b]; all share the fanouts.
  * Batches are independent units (section 4.2), so this is how several are kept in flight.

@@ -32,6 +32,7 @@ EXPORTS = [
     "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_validate", "smfg_graph_set_labels", "smfg_bounds",
     "smfg_workspace_create", "smfg_workspace_create_sized",
     "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
+    "smfg_sample_mfg_static",
     "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_sage_layer", "smfg_sage_pack_weights",
     "smfg_sage_packed_bytes", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
@@ -81,6 +82,7 @@ def lib() -> ctypes.CDLL:
         L.smfg_workspace_bytes.restype = i64
         L.smfg_sample_mfg.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32), i32, u64,
                                       ctypes.POINTER(_Output), vp]
+        L.smfg_sample_mfg_static.argtypes = [vp, vp, i32, ctypes.POINTER(i32), i32, u64, ctypes.POINTER(_Output), vp]
         L.smfg_sample_mfg_many.argtypes = [vp, pp, pp, ctypes.POINTER(i32), ctypes.POINTER(i32), i32,
                                            ctypes.POINTER(u64), ctypes.POINTER(_Output), i32, vp]
         L.smfg_gather_rows.argtypes = [vp, vp, vp, i64, vp, vp]
@@ -280,6 +282,19 @@ def sample_mfg(g: Graph, ws: Workspace, seeds: torch.Tensor, fanouts: Sequence[i
                                ctypes.c_uint64(rng_key & 0xFFFFFFFFFFFFFFFF), ctypes.byref(out.c),
                                _stream_ptr(stream))
     _check(rc, "smfg_sample_mfg")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def sample_mfg_static(g: Graph, seeds: torch.Tensor, fanouts: Sequence[int], rng_key: int, out: Output,
+                      stream: Optional[torch.cuda.Stream] = None) -> None:
+    """sample_mfg without a workspace: scratch is the library's fixed per-GPU array; allocates nothing."""
+    assert seeds.dtype == torch.int32 and seeds.is_contiguous()
+    rc = lib().smfg_sample_mfg_static(g.handle, _ptr(seeds), seeds.numel(), _fan(fanouts), len(fanouts),
+                                      ctypes.c_uint64(rng_key & 0xFFFFFFFFFFFFFFFF), ctypes.byref(out.c),
+                                      _stream_ptr(stream))
+    _check(rc, "smfg_sample_mfg_static")
 
 
 def _out_array(outs: Sequence[Output], with_features: bool = True):

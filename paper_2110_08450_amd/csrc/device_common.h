@@ -130,6 +130,13 @@ __device__ __forceinline__ uint32_t table_insert_min(const BatchCtx& B, uint32_t
   return 0u;
 }
 
+// Small fill kernel (used instead of a memset node where a caller may capture the stream).
+__global__ void __launch_bounds__(kThreads) k_fill_u32(uint32_t* p, int64_t n, uint32_t value) {
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < n;
+       i += static_cast<int64_t>(gridDim.x) * kThreads)
+    p[i] = value;
+}
+
 // ---- block scan ------------------------------------------------------------------------------
 // Exclusive scan over a block of kThreads values; returns the exclusive prefix, total in `total`.
 __device__ __forceinline__ unsigned long long block_exscan(unsigned long long x, unsigned long long* lds,

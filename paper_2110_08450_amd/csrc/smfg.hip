@@ -37,6 +37,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "smfg.h"
@@ -47,6 +48,11 @@
 #include "kernels_gather.h"
 #include "kernels_validate.h"
 #include "kernels_wide.h"
+
+// Scratch of smfg_sample_mfg_static: one copy per GPU, held until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; the device address is looked up once per
+// device (static_scratch_of) and that pointer is what the kernels and the fill receive.
+static __device__ __align__(256) unsigned char scratch[SMFG_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -239,6 +245,26 @@ void bind_workspace(smfg_workspace* ws, void* base) {
   p += ws->b_row;  // spare
   ws->tile_sums = reinterpret_cast<uint64_t*>(p); p += ws->b_tiles;
   ws->stile_sums = reinterpret_cast<uint64_t*>(p);
+}
+
+// Device address of this GPU's copy of `scratch`, looked up at the first call on the device (the
+// device must be current).  Each GPU has its own copy at its own address.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_of(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return SMFG_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_err(e);
+    if (!p) return SMFG_ERR_HIP_BASE;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return SMFG_OK;
 }
 
 // The gather launch shared by smfg_sample_mfg_many and smfg_gather_many.
@@ -602,6 +628,34 @@ int smfg_sample_mfg(const smfg_graph_t* g, smfg_workspace_t* ws, const int32_t* 
                     void* hip_stream) {
   if (!out) return SMFG_ERR_NULL_PTR;
   return smfg_sample_mfg_many(g, &ws, &d_seeds, &num_seeds, fanouts, L, &rng_key, out, 1, hip_stream);
+}
+
+int smfg_sample_mfg_static(const smfg_graph_t* g, const int32_t* d_seeds, int32_t num_seeds, const int32_t* fanouts,
+                           int32_t L, uint64_t rng_key, const smfg_output_t* out, void* hip_stream) {
+  if (!g || !out) return SMFG_ERR_NULL_PTR;
+  if (num_seeds < 0 || out->node_capacity < 1) return SMFG_ERR_INVALID_ARG;
+  // the workspace this call needs: the caller's node capacity bounds it, as in smfg_workspace_create
+  smfg_workspace ws;
+  int rc = plan_workspace(&ws, g, num_seeds, L, fanouts, out->node_capacity, 0);
+  if (rc != SMFG_OK) return rc;
+  if (ws.bytes > static_cast<int64_t>(SMFG_STATIC_SCRATCH_BYTES)) return SMFG_ERR_CAPACITY;
+  int cur = 0;
+  hipError_t e = hipGetDevice(&cur);
+  if (e != hipSuccess) return hip_err(e);
+  if (cur != g->device) (void)hipSetDevice(g->device);
+  void* base = nullptr;
+  rc = static_scratch_of(g->device, &base);
+  if (rc == SMFG_OK) {
+    bind_workspace(&ws, base);
+    // the array keeps what the last call left: the displacement notes must start out clear
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    k_fill_u32<<<blocks_for(ws.slot_entries, kThreads * 4, 1024), kThreads, 0, st>>>(ws.lostto, ws.slot_entries, 0u);
+    rc = hip_err(hipGetLastError());
+  }
+  if (cur != g->device) (void)hipSetDevice(cur);
+  if (rc != SMFG_OK) return rc;
+  smfg_workspace* wsp = &ws;
+  return smfg_sample_mfg_many(g, &wsp, &d_seeds, &num_seeds, fanouts, L, &rng_key, out, 1, hip_stream);
 }
 
 int smfg_gather_many(const smfg_graph_t* g, const smfg_output_t* outs, int32_t num_batches, int32_t L,

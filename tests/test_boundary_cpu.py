@@ -114,6 +114,7 @@ def test_graph_create_refuses_bad_arguments_before_touching_a_device():
                                  vp(ok_ptr), None) == smfg.ERR_INVALID_ARG
     assert L.smfg_sage_layer(vp(ok_ptr), vp(ok_ptr + 1), i64(8), vp(ok_ptr), i64(4), vp(ok_ptr), i64(4), 8,
                              vp(ok_ptr), None, 8, 0, vp(ok_ptr), 2, None) == smfg.ERR_INVALID_ARG
+    assert L.smfg_sample_mfg_static(None, vp(ok_ptr), 4, None, 1, ctypes.c_uint64(1), None, None) == smfg.ERR_NULL_PTR
     assert "internal" in smfg.strerror(smfg.ST_INTERNAL)
 
 
