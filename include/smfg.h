@@ -296,7 +296,9 @@ int smfg_read_counts(const smfg_output_t *out, int32_t L, int64_t *h_counts, voi
 #define SMFG_STAGE_GATHER 6
 #define SMFG_STAGE_AGGREGATE 7
 #define SMFG_STAGE_LAYER 8
-#define SMFG_NUM_STAGES 9
+#define SMFG_STAGE_PARTITION 9
+#define SMFG_STAGE_DEDUP 10
+#define SMFG_NUM_STAGES 11
 int smfg_profile_begin(int32_t level, int32_t max_records);
 int smfg_profile_end(double *stage_ms /* host [SMFG_NUM_STAGES] */,
                      int64_t *stage_launches /* host [SMFG_NUM_STAGES] */);

@@ -37,7 +37,7 @@ EXPORTS = [
     "smfg_sage_packed_bytes", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
 ]
 STAGES = ["clear", "seeds", "sample_insert", "flag_rows", "scan_tiles", "assemble", "gather",
-          "mean_aggregate", "sage_layer"]
+          "mean_aggregate", "sage_layer", "partition", "dedup_buckets"]
 
 
 class SmfgError(RuntimeError):

@@ -17,7 +17,6 @@ constexpr uint32_t kPend = 0x80000000u;     // table value / entry tag: a positi
 constexpr uint32_t kSlot = 0x40000000u;     // entry tag: index of the sample's table slot
 constexpr uint32_t kTagMask = 0xC0000000u;
 constexpr uint64_t kEmpty = ~0ull;
-constexpr uint32_t kMaxProbes = 4096;      // longest probe run before the table counts as full
 
 struct BatchCtx {
   const int32_t* seeds;
@@ -46,6 +45,10 @@ struct BatchCtx {
   uint32_t key0, key1;
   uint32_t table_shift;  // slot = hash >> shift
   uint32_t table_mask;
+  // partition path (no table): records of a hop grouped by hash bucket
+  uint64_t* rec;         // (node << 32 | value) per known node and per sample, bucket by bucket
+  uint32_t* hist;        // [blocks x buckets] records per (row block, bucket), later their offsets
+  uint32_t* bstart;      // [buckets + 1] first record of each bucket; [buckets + 1 .. 2 buckets + 1) bucket sizes
 };
 
 struct Launch {
@@ -61,11 +64,32 @@ struct Launch {
   int32_t h;       // current hop
   int32_t d;       // its fanout
   int32_t G;       // batches
+  int32_t lgB;     // partition path: log2 of the hash buckets of this hop
+  int32_t block_rows;  // partition path: destinations per row block of this hop
   BatchCtx b[SMFG_MAX_BATCHES];
 };
+static_assert(sizeof(Launch) <= 4096, "kernel arguments are limited to 4 KB");
+
+// Grids are one-dimensional with the batch as the fastest-varying part of the block index:
+// consecutive workgroups go to consecutive XCDs, so with 8 batches per call the blocks of one
+// batch share one XCD and its L2 (a locality preference only, nothing depends on it).
+__device__ __forceinline__ int batch_of_block(const Launch& P) { return static_cast<int>(blockIdx.x % static_cast<unsigned>(P.G)); }
+__device__ __forceinline__ int block_in_batch(const Launch& P) { return static_cast<int>(blockIdx.x / static_cast<unsigned>(P.G)); }
+__device__ __forceinline__ int blocks_per_batch(const Launch& P) { return static_cast<int>(gridDim.x / static_cast<unsigned>(P.G)); }
 
 __device__ __forceinline__ int64_t status_of(const BatchCtx& B, int L) {
   return __hip_atomic_load(&B.counts[2 * L + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The same answer for every thread of the block (other blocks may set the status while this one
+// starts, and kernels that synchronise must leave as whole blocks).
+__device__ __forceinline__ bool block_has_status(const BatchCtx& B, int L) {
+  __shared__ int st_lds;
+  if (threadIdx.x == 0) st_lds = status_of(B, L) != 0 ? 1 : 0;
+  __syncthreads();
+  const bool r = st_lds != 0;
+  __syncthreads();
+  return r;
 }
 
 __device__ __forceinline__ void set_status(const BatchCtx& B, int L, int64_t code) {
@@ -109,10 +133,10 @@ __device__ __forceinline__ uint32_t table_insert_min(const BatchCtx& B, uint32_t
   const unsigned long long mine = (static_cast<unsigned long long>(key) << 32) | val;
   uint32_t s = hash_slot(key, B.table_shift);
   full = false;
-  // The table has at least two slots per node of capacity, so a probe run this long only occurs
-  // when far more distinct nodes arrive than the capacity allows: report the table as full.
-  const uint32_t max_probes = B.table_mask < kMaxProbes ? B.table_mask + 1u : kMaxProbes;
-  for (uint32_t probes = 0; probes < max_probes; ++probes) {
+  // A probe run that has seen every slot means more distinct nodes than slots, i.e. more than
+  // twice the node capacity: only then is the table reported as full.  (Node ids whose hashes
+  // share their leading bits make long runs, which cost time but never a wrong answer.)
+  for (uint64_t probes = 0; probes <= B.table_mask; ++probes) {
     unsigned long long old = atomicCAS(&T[s], kEmpty, mine);
     if (old == kEmpty) {
       slot = s;

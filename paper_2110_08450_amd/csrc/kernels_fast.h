@@ -1,5 +1,7 @@
-// libsmfg fast path (fanouts up to SMFG_MAX_FANOUT): table clear, seed insert, and per hop
-// sample_insert / flag_rows / scan_tiles / assemble over padded sample positions pos = i * d + s.
+// libsmfg fast path (fanouts up to SMFG_MAX_FANOUT), samples at padded positions pos = i * d + s.
+// This file: the per-destination draw shared by both dedup strategies, the table strategy's
+// clear / seed insert / sample_insert, and the flag_rows / scan_tiles / assemble passes that turn
+// first-appearance information into local ids (shared by both strategies).
 #ifndef SMFG_KERNELS_FAST_H_
 #define SMFG_KERNELS_FAST_H_
 
@@ -8,21 +10,34 @@
 namespace smfg_dev {
 
 __global__ void __launch_bounds__(kThreads) k_clear(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
+  const BatchCtx& B = P.b[batch_of_block(P)];
   const size_t n = static_cast<size_t>(B.table_mask) + 1;
-  for (size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x; i < n;
-       i += static_cast<size_t>(gridDim.x) * kThreads)
+  const size_t stride = static_cast<size_t>(blocks_per_batch(P)) * kThreads;
+  for (size_t i = static_cast<size_t>(block_in_batch(P)) * kThreads + threadIdx.x; i < n; i += stride)
     B.table[i] = kEmpty;
-  if (blockIdx.x == 0) {
+  if (block_in_batch(P) == 0) {
     const int m = 2 * P.L + 2;
     for (int q = threadIdx.x; q < m; q += kThreads) B.counts[q] = (q == 0) ? B.num_seeds : 0;
   }
 }
 
+// ys = y[ids[:batch_size]] (Listing 1): the seeds are the first ids.
+__device__ __forceinline__ void copy_label(const Launch& P, const BatchCtx& B, int i, int32_t v) {
+  const uint8_t* src = P.labels + static_cast<int64_t>(v) * P.label_bytes;
+  uint8_t* dst = B.labels + static_cast<int64_t>(i) * P.label_bytes;
+  switch (P.label_bytes) {
+    case 8: *reinterpret_cast<uint64_t*>(dst) = *reinterpret_cast<const uint64_t*>(src); break;
+    case 4: *reinterpret_cast<uint32_t*>(dst) = *reinterpret_cast<const uint32_t*>(src); break;
+    case 2: *reinterpret_cast<uint16_t*>(dst) = *reinterpret_cast<const uint16_t*>(src); break;
+    default: *dst = *src; break;
+  }
+}
+
 // M starts with the destination nodes of hop 0 in the order given (procedure OneHopMFG).
 __global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
-  for (int i = blockIdx.x * kThreads + threadIdx.x; i < B.num_seeds; i += gridDim.x * kThreads) {
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  const int stride = blocks_per_batch(P) * kThreads;
+  for (int i = block_in_batch(P) * kThreads + threadIdx.x; i < B.num_seeds; i += stride) {
     const int32_t v = B.seeds[i];
     if (v < 0 || static_cast<int64_t>(v) >= P.num_nodes) {
       set_status(B, P.L, SMFG_ST_SEED_OUT_OF_RANGE);
@@ -34,71 +49,86 @@ __global__ void __launch_bounds__(kThreads) k_insert_seeds(const Launch P) {
     if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
     else if (prev != 0xFFFFFFFFu) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
     B.node_ids[i] = v;
-    if (B.labels) {  // ys = y[ids[:batch_size]] (Listing 1): the seeds are the first ids
-      const uint8_t* src = P.labels + static_cast<int64_t>(v) * P.label_bytes;
-      uint8_t* dst = B.labels + static_cast<int64_t>(i) * P.label_bytes;
-      switch (P.label_bytes) {
-        case 8: *reinterpret_cast<uint64_t*>(dst) = *reinterpret_cast<const uint64_t*>(src); break;
-        case 4: *reinterpret_cast<uint32_t*>(dst) = *reinterpret_cast<const uint32_t*>(src); break;
-        case 2: *reinterpret_cast<uint16_t*>(dst) = *reinterpret_cast<const uint16_t*>(src); break;
-        default: *dst = *src; break;
-      }
-    }
+    if (B.labels) copy_label(P, B, i, v);
   }
 }
 
 // d lanes cooperate on one destination, lane s of the group owns slot s; a wave holds
 // floor(64 / d) groups (its last 64 mod d lanes idle).
+struct LaneGroups {
+  int d, per_wave, per_block, grp, s, gbase, row_in_block;
+  bool lane_used;
+  unsigned long long gmask;
+  __device__ __forceinline__ explicit LaneGroups(int d_) {
+    const int lane = threadIdx.x & 63;
+    d = d_;
+    per_wave = 64 / d;                 // destinations per wave
+    per_block = per_wave * (kThreads / 64);
+    grp = lane / d;
+    s = lane - grp * d;
+    lane_used = grp < per_wave;
+    gbase = grp * d;                   // first lane of the group within the wave
+    gmask = (1ull << d) - 1ull;
+    row_in_block = (threadIdx.x >> 6) * per_wave + grp;
+  }
+};
+
+// The draw for destination i (section 2.2: at most d neighbours, uniformly, without replacement):
+// lane s of the destination's group ends up with the global id g of the s-th pick, if s < k.
+// `row` tells whether this lane's group has a destination at all; the whole wave must call.
+// Returns true for lanes that hold a sample.
+__device__ __forceinline__ bool draw_neighbour(const Launch& P, const BatchCtx& B, const LaneGroups& G, int i,
+                                               bool row, uint32_t& v, uint32_t& k, uint32_t& g) {
+  const int d = G.d, s = G.s;
+  uint32_t deg = 0;
+  int64_t a = 0;
+  v = 0;
+  if (row) {
+    v = static_cast<uint32_t>(B.node_ids[i]);
+    a = P.indptr[v];
+    deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
+  }
+  const bool floyd = row && deg > static_cast<uint32_t>(d);
+  k = floyd ? static_cast<uint32_t>(d) : deg;
+  uint32_t p = static_cast<uint32_t>(s);  // whole row in CSR order when deg <= d
+  uint32_t t = 0, j = 0;
+  if (floyd) {
+    const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), static_cast<uint32_t>(s) >> 2,
+                                   B.key0, B.key1, static_cast<uint32_t>(s) & 3u);
+    j = deg - static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
+    t = __umulhi(w, j + 1u);  // index in [0, j]
+  }
+  // Floyd's subset algorithm, resolved slot by slot: pick t_s unless an earlier slot holds it,
+  // then pick j_s.  The membership test is a linear search over the lanes (the array set).
+  if (__any(floyd)) {
+    for (int q = 0; q < d; ++q) {
+      const uint32_t tq = __shfl(t, G.gbase + q, 64);
+      const bool hit = floyd && s < q && p == tq;
+      const unsigned long long bal = (__ballot(hit) >> G.gbase) & G.gmask;
+      if (floyd && s == q) p = bal ? j : tq;
+    }
+  }
+  const bool has = row && static_cast<uint32_t>(s) < k;
+  g = 0;
+  // a neighbour id is read once per batch: keep it out of the way of data that is reused
+  if (has) g = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + p)));
+  return has;
+}
+
 __global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
+  const BatchCtx& B = P.b[batch_of_block(P)];
   // other blocks of this launch may set the status at any time: leave as whole waves only, the
   // lanes below talk to each other
   if (__any(status_of(B, P.L) != 0)) return;
   const int n = static_cast<int>(B.counts[P.h]);
-  const int d = P.d;
-  const int lane = threadIdx.x & 63;
-  const int per_wave = 64 / d;                 // destinations per wave
-  const int per_block = per_wave * (kThreads / 64);
-  const int grp = lane / d;
-  const int s = lane - grp * d;
-  const bool lane_used = grp < per_wave;
-  const int gbase = grp * d;                   // first lane of the group within the wave
-  const unsigned long long gmask = (1ull << d) - 1ull;
-  const int row_in_block = (threadIdx.x >> 6) * per_wave + grp;
-
-  for (int i0 = blockIdx.x * per_block; i0 < n; i0 += gridDim.x * per_block) {
-    const int i = i0 + row_in_block;
-    const bool row = lane_used && i < n;
-    uint32_t v = 0, deg = 0;
-    int64_t a = 0;
-    if (row) {
-      v = static_cast<uint32_t>(B.node_ids[i]);
-      a = P.indptr[v];
-      deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
-    }
-    const bool floyd = row && deg > static_cast<uint32_t>(d);
-    const uint32_t k = floyd ? static_cast<uint32_t>(d) : deg;
-    uint32_t p = static_cast<uint32_t>(s);  // whole row in CSR order when deg <= d
-    uint32_t t = 0, j = 0;
-    if (floyd) {
-      const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), static_cast<uint32_t>(s) >> 2,
-                                     B.key0, B.key1, static_cast<uint32_t>(s) & 3u);
-      j = deg - static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
-      t = __umulhi(w, j + 1u);  // index in [0, j]
-    }
-    // Floyd's subset algorithm, resolved slot by slot: pick t_s unless an earlier slot holds it,
-    // then pick j_s.  The membership test is a linear search over the lanes (the array set).
-    if (__any(floyd)) {
-      for (int q = 0; q < d; ++q) {
-        const uint32_t tq = __shfl(t, gbase + q, 64);
-        const bool hit = floyd && s < q && p == tq;
-        const unsigned long long bal = (__ballot(hit) >> gbase) & gmask;
-        if (floyd && s == q) p = bal ? j : tq;
-      }
-    }
-    if (row && static_cast<uint32_t>(s) < k) {
-      const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
-      const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(d) + static_cast<uint32_t>(s);
+  const LaneGroups G(P.d);
+  const int stride = blocks_per_batch(P) * G.per_block;
+  for (int i0 = block_in_batch(P) * G.per_block; i0 < n; i0 += stride) {
+    const int i = i0 + G.row_in_block;
+    const bool row = G.lane_used && i < n;
+    uint32_t v, k, g;
+    if (draw_neighbour(P, B, G, i, row, v, k, g)) {
+      const uint32_t pos = static_cast<uint32_t>(i) * static_cast<uint32_t>(G.d) + static_cast<uint32_t>(G.s);
       uint32_t slot;
       bool full;
       const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
@@ -115,7 +145,7 @@ __global__ void __launch_bounds__(kThreads) k_sample_insert(const Launch P) {
       B.ent[pos] = e;
       B.gsrc[pos] = static_cast<int32_t>(g);
     }
-    if (row && s == 0) B.rowk[i] = static_cast<int32_t>(k);
+    if (row && G.s == 0) B.rowk[i] = static_cast<int32_t>(k);
   }
 }
 
@@ -131,25 +161,31 @@ struct DivD {
 };
 
 // One block per tile of kTileRows destinations.  The padded samples of a tile are one contiguous
-// span of ent / lostto, read flat and coalesced.
+// span of ent (and lostto), read flat and coalesced.  NOTES: the table strategy's displacement
+// notes are applied (a displaced owner becomes a pointer) and cleared; the partition strategy
+// writes final states into ent and has no notes.
+template <bool NOTES>
 __global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
   __shared__ int k_lds[kTileRows];
   __shared__ unsigned int mask_lds[kTileRows];
   static_assert(kTileRows == kThreads, "one row per thread");
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) {
-    // a failed sample_insert may have left displacement notes behind: wipe them all
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < B.lostto_entries;
-         q += static_cast<int64_t>(gridDim.x) * kThreads)
-      B.lostto[q] = 0u;
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  const int nblocks = blocks_per_batch(P);
+  if (block_has_status(B, P.L)) {
+    if (NOTES) {
+      // a failed sample_insert may have left displacement notes behind: wipe them all
+      for (int64_t q = static_cast<int64_t>(block_in_batch(P)) * kThreads + threadIdx.x; q < B.lostto_entries;
+           q += static_cast<int64_t>(nblocks) * kThreads)
+        B.lostto[q] = 0u;
+    }
     return;
   }
   const int n = static_cast<int>(B.counts[P.h]);
   const uint32_t d = static_cast<uint32_t>(P.d);
   const DivD div(d);
   const int tiles = (n + kTileRows - 1) / kTileRows;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (int tile = block_in_batch(P); tile < tiles; tile += nblocks) {
     const int i0 = tile * kTileRows;
     const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
     const int tr = threadIdx.x;
@@ -165,7 +201,7 @@ __global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint32_t idx = base + u * kThreads;
-        lost[u] = idx < cnt ? B.lostto[pos0 + idx] : 0u;
+        lost[u] = (NOTES && idx < cnt) ? B.lostto[pos0 + idx] : 0u;
         e[u] = idx < cnt ? B.ent[pos0 + idx] : 0u;
       }
 #pragma unroll
@@ -175,7 +211,7 @@ __global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
           uint32_t r, sl;
           div.split(idx, r, sl);
           if (sl < static_cast<uint32_t>(k_lds[r])) {
-            if (lost[u] != 0u) {  // displaced by the sample at lost[u]: follow it later
+            if (NOTES && lost[u] != 0u) {  // displaced by the sample at lost[u]: follow it later
               B.ent[pos0 + idx] = lost[u];
               B.lostto[pos0 + idx] = 0u;
             } else if ((e[u] & kTagMask) == kSlot) {
@@ -201,8 +237,8 @@ __global__ void __launch_bounds__(kThreads) k_flag_rows(const Launch P) {
 
 __global__ void __launch_bounds__(kThreads) k_scan_tiles(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const int tiles = (n + kTileRows - 1) / kTileRows;
   unsigned long long carry = 0;
@@ -226,19 +262,22 @@ __global__ void __launch_bounds__(kThreads) k_scan_tiles(const Launch P) {
 }
 
 // One block per tile of kTileRows destinations; samples are walked flat like in k_flag_rows.
+// PUBLISH: first appearances also write their final id into their slot of the dedup table (the
+// table strategy, all hops but the last); then the tag-01 entries carry that slot.
+template <bool PUBLISH>
 __global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
   __shared__ int k_lds[kTileRows];
   __shared__ unsigned int mask_lds[kTileRows];
   __shared__ unsigned int off_lds[kTileRows];   // global edge offset of the destination
   __shared__ unsigned int rank_lds[kTileRows];  // local id of the destination's first new node
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const uint32_t d = static_cast<uint32_t>(P.d);
   const DivD div(d);
-  const bool last = P.h == P.L - 1;  // nodes found in the last hop are never looked up again
   const int tiles = (n + kTileRows - 1) / kTileRows;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  const int nblocks = blocks_per_batch(P);
+  for (int tile = block_in_batch(P); tile < tiles; tile += nblocks) {
     const int i0 = tile * kTileRows;
     const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
     const int tr = threadIdx.x;
@@ -299,7 +338,7 @@ __global__ void __launch_bounds__(kThreads) k_assemble(const Launch P) {
         if ((e[u] & kTagMask) == kSlot) {  // first appearance: rank among the new nodes of this hop
           local = rank_lds[r[u]] + __popc(mask_lds[r[u]] & ((1u << sl[u]) - 1u));
           B.node_ids[local] = static_cast<int32_t>(g[u]);
-          if (!last) B.table[e[u] & ~kTagMask] = (static_cast<uint64_t>(g[u]) << 32) | local;
+          if (PUBLISH) B.table[e[u] & ~kTagMask] = (static_cast<uint64_t>(g[u]) << 32) | local;
         } else if (dup[u]) {
           uint32_t qq = q[u], qqi = qi[u];
           uint2 m = mn[u];

@@ -1,0 +1,298 @@
+// libsmfg partition strategy for the dedup of a hop (fanouts up to SMFG_MAX_FANOUT, hops whose
+// nodes + samples fit kPartMaxRecords).
+//
+// Procedure OneHopMFG keeps one map from global to local ids and gives a node its local id at the
+// first encounter.  Here the map never exists as one structure in memory.  Per hop:
+//   sample_hist   draws the neighbours (as k_sample_insert does) into gsrc and counts, per block
+//                 of destinations, how many records fall into each hash bucket; a record is
+//                 (node, value): one per known node (value = its local id) and one per sample
+//                 (value = tag | scan position);
+//   scan_hist     turns the counts of a bucket over the row blocks into offsets, bucket sizes;
+//   scatter       moves the records into their buckets (one contiguous range of `rec` each);
+//   dedup_buckets one block per bucket builds a hash table of the bucket's nodes in LDS, keeping
+//                 the smallest value per node (a known node's local id always wins, else the
+//                 earliest scan position), then writes every sample's state into ent[position]:
+//                 the final local id (known node), "first appearance", or the position of the
+//                 first appearance.
+// flag_rows / scan_tiles / assemble then number the first appearances in scan order, exactly the
+// ids the serial first-encounter rule gives.  Which thread inserts first never matters: only
+// minima are kept.  All global traffic but the neighbour reads and the scattered 4-byte state
+// writes is streaming, and there are no global atomics.
+#ifndef SMFG_KERNELS_PART_H_
+#define SMFG_KERNELS_PART_H_
+
+#include "device_common.h"
+#include "kernels_fast.h"
+
+namespace smfg_dev {
+
+constexpr int kPartMaxLgB = 10;                     // at most 1024 buckets per hop
+constexpr int kPartTableLg = 12;                    // LDS table: 4096 slots of 8 bytes
+constexpr uint32_t kPartSlots = 1u << kPartTableLg;
+constexpr int kPartBucketRecords = 2048;            // buckets are sized for at most this many on average
+constexpr int64_t kPartMaxRecords = static_cast<int64_t>(kPartBucketRecords) << kPartMaxLgB;
+constexpr int kPartMaxRowBlocks = 512;              // row blocks per batch and hop (plus a ragged one)
+constexpr uint32_t kPartHash = 0x9E3779B1u;         // odd: node -> node * kPartHash is a bijection on 32 bits
+
+__device__ __forceinline__ uint32_t part_bucket(uint32_t node, int lgB) {
+  return lgB == 0 ? 0u : (node * kPartHash) >> (32 - lgB);
+}
+
+// counts <- (n_0, 0, ..., status 0); node_ids[0, n_0) <- seeds; labels of the seeds.  Seeds are
+// range-checked by the first hop's k_sample_hist, which runs after the status word is zero.
+__global__ void __launch_bounds__(kThreads) k_begin(const Launch P) {
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_in_batch(P) == 0) {
+    const int m = 2 * P.L + 2;
+    for (int q = threadIdx.x; q < m; q += kThreads) B.counts[q] = (q == 0) ? B.num_seeds : 0;
+  }
+  const int stride = blocks_per_batch(P) * kThreads;
+  for (int i = block_in_batch(P) * kThreads + threadIdx.x; i < B.num_seeds; i += stride) {
+    const int32_t v = B.seeds[i];
+    B.node_ids[i] = v;
+    if (B.labels && v >= 0 && static_cast<int64_t>(v) < P.num_nodes) copy_label(P, B, i, v);
+  }
+}
+
+// Samples of the block's destinations -> gsrc, rowk; per-bucket record counts -> hist row.
+__global__ void __launch_bounds__(kThreads) k_sample_hist(const Launch P) {
+  __shared__ uint32_t hist[1 << kPartMaxLgB];
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  const int blk = block_in_batch(P);
+  if (block_has_status(B, P.L)) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int r0 = blk * P.block_rows;
+  if (r0 >= n) return;
+  const int r1 = r0 + P.block_rows < n ? r0 + P.block_rows : n;
+  const int nB = 1 << P.lgB;
+  for (int b = threadIdx.x; b < nB; b += kThreads) hist[b] = 0u;
+  __syncthreads();
+  const LaneGroups G(P.d);
+  for (int i0 = r0; i0 < r1; i0 += G.per_block) {
+    const int i = i0 + G.row_in_block;
+    bool row = G.lane_used && i < r1;
+    if (P.h == 0 && row) {  // the seeds are caller data: none may index the graph unchecked
+      const int32_t seed = B.node_ids[i];
+      if (seed < 0 || static_cast<int64_t>(seed) >= P.num_nodes) {
+        set_status(B, P.L, SMFG_ST_SEED_OUT_OF_RANGE);
+        row = false;
+      }
+    }
+    uint32_t v, k, g;
+    if (draw_neighbour(P, B, G, i, row, v, k, g)) {
+      B.gsrc[static_cast<uint32_t>(i) * static_cast<uint32_t>(G.d) + static_cast<uint32_t>(G.s)] = static_cast<int32_t>(g);
+      atomicAdd(&hist[part_bucket(g, P.lgB)], 1u);
+    }
+    if (row && G.s == 0) {
+      B.rowk[i] = static_cast<int32_t>(k);
+      atomicAdd(&hist[part_bucket(v, P.lgB)], 1u);  // the destination itself, a known node
+    }
+  }
+  __syncthreads();
+  uint32_t* out = B.hist + static_cast<size_t>(blk) * nB;
+  for (int b = threadIdx.x; b < nB; b += kThreads) out[b] = hist[b];
+}
+
+// One thread per bucket: counts of the bucket over the row blocks -> exclusive offsets; bucket size.
+__global__ void __launch_bounds__(kThreads) k_scan_hist(const Launch P) {
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (status_of(B, P.L) != 0) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int blocks = (n + P.block_rows - 1) / P.block_rows;
+  const int nB = 1 << P.lgB;
+  const int b = block_in_batch(P) * kThreads + threadIdx.x;
+  if (b >= nB) return;
+  uint32_t run = 0;
+  uint32_t* col = B.hist + b;
+  int j = 0;
+  constexpr int U = 8;
+  for (; j + U <= blocks; j += U) {
+    uint32_t t[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) t[u] = col[static_cast<size_t>(j + u) * nB];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      col[static_cast<size_t>(j + u) * nB] = run;
+      run += t[u];
+    }
+  }
+  for (; j < blocks; ++j) {
+    const uint32_t t = col[static_cast<size_t>(j) * nB];
+    col[static_cast<size_t>(j) * nB] = run;
+    run += t;
+  }
+  B.bstart[nB + 1 + b] = run;  // bucket size
+}
+
+// Records of the block's destinations -> their buckets.
+__global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
+  __shared__ uint32_t cur[1 << kPartMaxLgB];
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const int blk = block_in_batch(P);
+  const int n = static_cast<int>(B.counts[P.h]);
+  const int r0 = blk * P.block_rows;
+  if (r0 >= n) return;
+  const int r1 = r0 + P.block_rows < n ? r0 + P.block_rows : n;
+  const int nB = 1 << P.lgB;
+  // first record of every bucket: exclusive scan of the bucket sizes, four buckets per thread
+  {
+    constexpr int per = (1 << kPartMaxLgB) / kThreads;
+    uint32_t sz[per];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      sz[u] = b < nB ? B.bstart[nB + 1 + b] : 0u;
+      mine += sz[u];
+    }
+    unsigned long long total;
+    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+    const uint32_t* offs = B.hist + static_cast<size_t>(blk) * nB;
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      if (b < nB) {
+        cur[b] = pre + offs[b];
+        if (blk == 0) B.bstart[b] = pre;
+      }
+      pre += sz[u];
+    }
+    if (blk == 0 && threadIdx.x == 0) B.bstart[nB] = static_cast<uint32_t>(total);
+  }
+  __syncthreads();
+  const uint32_t d = static_cast<uint32_t>(P.d);
+  const DivD div(d);
+  // known nodes: destination i has local id i
+  for (int i = r0 + threadIdx.x; i < r1; i += kThreads) {
+    const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
+    const uint32_t at = atomicAdd(&cur[part_bucket(v, P.lgB)], 1u);
+    B.rec[at] = (static_cast<unsigned long long>(v) << 32) | static_cast<uint32_t>(i);
+  }
+  // samples, flat over the padded positions of the block's destinations
+  const uint32_t pos0 = static_cast<uint32_t>(r0) * d;
+  const uint32_t cnt = static_cast<uint32_t>(r1 - r0) * d;
+  constexpr int U = 4;
+  for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
+    uint32_t g[U], k[U], sl[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t idx = base + u * kThreads;
+      g[u] = 0u;
+      k[u] = 0u;
+      sl[u] = 0u;
+      if (idx < cnt) {
+        uint32_t r;
+        div.split(idx, r, sl[u]);
+        k[u] = static_cast<uint32_t>(B.rowk[r0 + static_cast<int>(r)]);
+        g[u] = static_cast<uint32_t>(B.gsrc[pos0 + idx]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t idx = base + u * kThreads;
+      if (idx < cnt && sl[u] < k[u]) {
+        const uint32_t at = atomicAdd(&cur[part_bucket(g[u], P.lgB)], 1u);
+        B.rec[at] = (static_cast<unsigned long long>(g[u]) << 32) | (kPend | (pos0 + idx));
+      }
+    }
+  }
+}
+
+// One block per bucket.  All records of a node are in one bucket, so the bucket's table in LDS
+// sees every occurrence of its nodes.  A bucket with more records than the table takes is
+// handled in 2^lgR rounds, round r taking the nodes whose next lgR hash bits equal r; should a
+// round still overflow (skewed bits), the bucket starts over with one more bit.  With
+// 32 - lgB - lgR <= kPartTableLg bits left every node of a round has a slot of its own (the hash
+// is a bijection), so the retries end.
+__global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
+  __shared__ unsigned long long tab[kPartSlots];
+  __shared__ int overflow_lds;
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const uint32_t bucket = static_cast<uint32_t>(block_in_batch(P));
+  const uint32_t nB = 1u << P.lgB;
+  if (bucket >= nB) return;
+  const uint32_t rec0 = B.bstart[bucket];
+  const uint32_t rec1 = rec0 + B.bstart[nB + 1 + bucket];
+  const uint32_t cnt = rec1 - rec0;
+  if (cnt == 0) return;
+  const int free_bits = 32 - P.lgB;  // hash bits below the bucket's
+  const int max_lgR = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
+  int lgR = 0;
+  while (lgR < max_lgR && (cnt >> lgR) > kPartSlots / 2) ++lgR;
+  for (;;) {
+    bool failed = false;
+    const int rem = free_bits - lgR;  // hash bits below the round's
+    const uint32_t rounds = 1u << lgR;
+    for (uint32_t round = 0; round < rounds && !failed; ++round) {
+      for (uint32_t q = threadIdx.x; q < kPartSlots; q += kThreads) tab[q] = kEmpty;
+      if (threadIdx.x == 0) overflow_lds = 0;
+      __syncthreads();
+      for (uint32_t r = rec0 + threadIdx.x; r < rec1; r += kThreads) {
+        const unsigned long long mine = B.rec[r];
+        const uint32_t node = static_cast<uint32_t>(mine >> 32);
+        const uint32_t hsh = node * kPartHash;
+        if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
+        uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
+        uint32_t probes = 0;
+        for (; probes < kPartSlots; ++probes) {
+          const unsigned long long old = atomicCAS(&tab[sl], kEmpty, mine);
+          if (old == kEmpty) break;
+          if (static_cast<uint32_t>(old >> 32) == node) {
+            if (old > mine) atomicMin(&tab[sl], mine);
+            break;
+          }
+          sl = (sl + 1u) & (kPartSlots - 1u);
+        }
+        if (probes == kPartSlots) overflow_lds = 1;
+      }
+      __syncthreads();
+      failed = overflow_lds != 0;
+      if (!failed) {
+        for (uint32_t r = rec0 + threadIdx.x; r < rec1; r += kThreads) {
+          const unsigned long long mine = B.rec[r];
+          const uint32_t node = static_cast<uint32_t>(mine >> 32);
+          const uint32_t val = static_cast<uint32_t>(mine);
+          const uint32_t hsh = node * kPartHash;
+          if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
+          uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
+          uint32_t least = 0u;
+          uint32_t probes = 0;
+          for (; probes < kPartSlots; ++probes) {
+            const unsigned long long t = tab[sl];
+            if (static_cast<uint32_t>(t >> 32) == node) {
+              least = static_cast<uint32_t>(t);
+              break;
+            }
+            sl = (sl + 1u) & (kPartSlots - 1u);
+          }
+          if (probes == kPartSlots) {  // every inserted node is found again
+            set_status(B, P.L, SMFG_ST_INTERNAL);
+            continue;
+          }
+          if (val < kPend) {
+            // a known node: two of them with one id can only be a repeated seed
+            if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
+          } else {
+            // least < kPend: the node's final local id; least == val: this sample is the node's
+            // first appearance; else least names the position of the first appearance
+            B.ent[val & ~kTagMask] = least == val ? kSlot : least;
+          }
+        }
+      }
+      __syncthreads();
+    }
+    if (!failed) break;
+    if (lgR >= max_lgR) {  // cannot overflow with a slot per node
+      if (threadIdx.x == 0) set_status(B, P.L, SMFG_ST_INTERNAL);
+      break;
+    }
+    ++lgR;
+  }
+}
+
+}  // namespace smfg_dev
+
+#endif  // SMFG_KERNELS_PART_H_

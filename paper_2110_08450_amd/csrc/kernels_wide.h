@@ -13,12 +13,12 @@ constexpr int kWideTile = 4 * kThreads;  // samples per flat tile
 // Degree, sample count and row start per destination; in-tile scan of the sample counts.
 __global__ void __launch_bounds__(kThreads) k_count_rows(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const int d = P.d;
   const int tiles = (n + kTileRows - 1) / kTileRows;
-  for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (int tile = block_in_batch(P); tile < tiles; tile += blocks_per_batch(P)) {
     const int i = tile * kTileRows + threadIdx.x;
     uint32_t k = 0;
     if (i < n) {
@@ -41,8 +41,8 @@ __global__ void __launch_bounds__(kThreads) k_count_rows(const Launch P) {
 // Exclusive scan of the per-tile sample counts; E_h and its capacity checks.
 __global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const int tiles = (n + kTileRows - 1) / kTileRows;
   unsigned long long carry = 0;
@@ -66,14 +66,14 @@ __global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
 // One wave per destination; lane l of round r owns slot s = 64 r + l.
 __global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P) {
   __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
-  const BatchCtx& B = P.b[blockIdx.y];
+  const BatchCtx& B = P.b[batch_of_block(P)];
   if (__any(status_of(B, P.L) != 0)) return;  // whole waves only: the lanes below cooperate
   const int n = static_cast<int>(B.counts[P.h]);
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* picks = picks_lds[wave];
-  const int waves_total = gridDim.x * (kThreads / 64);
-  for (int i = blockIdx.x * (kThreads / 64) + wave; i < n; i += waves_total) {
+  const int waves_total = blocks_per_batch(P) * (kThreads / 64);
+  for (int i = block_in_batch(P) * (kThreads / 64) + wave; i < n; i += waves_total) {
     const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
     const int64_t a = B.rowstart[i];
     const uint32_t deg = static_cast<uint32_t>(B.rowdeg[i]);
@@ -127,16 +127,16 @@ __global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P)
 // Flat over the samples: first appearances, their in-tile ranks, per-tile totals.
 __global__ void __launch_bounds__(kThreads) k_flag_flat(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) {
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < B.lostto_entries;
-         q += static_cast<int64_t>(gridDim.x) * kThreads)
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) {
+    for (int64_t q = static_cast<int64_t>(block_in_batch(P)) * kThreads + threadIdx.x; q < B.lostto_entries;
+         q += static_cast<int64_t>(blocks_per_batch(P)) * kThreads)
       B.lostto[q] = 0u;
     return;
   }
   const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = block_in_batch(P); tile < tiles; tile += blocks_per_batch(P)) {
     const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
     uint32_t first[4];
     uint32_t mine = 0;
@@ -170,8 +170,8 @@ __global__ void __launch_bounds__(kThreads) k_flag_flat(const Launch P) {
 // Exclusive scan of the per-tile counts of new nodes; n_{h+1} and its capacity check.
 __global__ void __launch_bounds__(kThreads) k_scan_flat_tiles(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
-  const BatchCtx& B = P.b[blockIdx.y];
-  if (status_of(B, P.L) != 0) return;
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
@@ -193,13 +193,13 @@ __global__ void __launch_bounds__(kThreads) k_scan_flat_tiles(const Launch P) {
 
 // Flat over the samples: final local ids -> block indices; first appearances publish themselves.
 __global__ void __launch_bounds__(kThreads) k_assemble_flat(const Launch P) {
-  const BatchCtx& B = P.b[blockIdx.y];
+  const BatchCtx& B = P.b[batch_of_block(P)];
   if (status_of(B, P.L) != 0) return;
   const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
   const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const bool last = P.h == P.L - 1;
   const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = block_in_batch(P); tile < tiles; tile += blocks_per_batch(P)) {
     const uint32_t tpre = n + static_cast<uint32_t>(B.stile_sums[tile]);
     const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
 #pragma unroll

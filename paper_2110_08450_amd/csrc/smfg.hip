@@ -46,6 +46,7 @@
 #include "kernels_aggregate.h"
 #include "kernels_fast.h"
 #include "kernels_gather.h"
+#include "kernels_part.h"
 #include "kernels_validate.h"
 #include "kernels_wide.h"
 
@@ -142,7 +143,11 @@ struct smfg_workspace {
   int64_t node_capacity;
   int64_t slot_entries;  // capacity of the per-sample arrays
   int64_t bytes;
-  int64_t b_table, b_slot, b_row, b_tiles, b_stiles;  // byte sizes of the parts of the slab
+  // partition strategy (no dedup table) or table strategy; fixed when the workspace is planned
+  bool part;
+  int64_t rec_entries;   // capacity of rec: known nodes + samples of a hop
+  int64_t hist_entries;  // capacity of hist: row blocks x buckets of a hop
+  int64_t b_table, b_slot, b_row, b_tiles, b_stiles, b_rec, b_hist, b_bstart;  // byte sizes of the slab's parts
   uint32_t table_log2;
   void* slab;
   uint64_t* table;
@@ -157,6 +162,9 @@ struct smfg_workspace {
   int32_t* rowdeg;
   uint32_t* rank;
   uint64_t* stile_sums;
+  uint64_t* rec;
+  uint32_t* hist;
+  uint32_t* bstart;
 };
 
 namespace {
@@ -193,6 +201,68 @@ int check_fanouts(int32_t L, const int32_t* fanouts, bool* wide = nullptr) {
 
 inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 
+// Launch shape of one hop under the partition strategy: 2^lgB hash buckets sized for at most
+// kPartBucketRecords records on average in the worst case, destinations cut into at most
+// kPartMaxRowBlocks (+1) row blocks that are whole multiples of what a thread block draws at once.
+struct HopPlan {
+  int lgB;
+  int block_rows;
+  int64_t row_blocks;
+};
+
+HopPlan plan_hop(int64_t max_rows, int d) {
+  HopPlan hp;
+  const int64_t records = max_rows * (1 + d);
+  hp.lgB = 0;
+  while (hp.lgB < kPartMaxLgB && (records >> hp.lgB) > kPartBucketRecords) ++hp.lgB;
+  hp.block_rows = (64 / d) * (kThreads / 64);
+  while ((max_rows + hp.block_rows - 1) / hp.block_rows > kPartMaxRowBlocks) hp.block_rows *= 2;
+  hp.row_blocks = (max_rows + hp.block_rows - 1) / hp.block_rows;
+  if (hp.row_blocks < 1) hp.row_blocks = 1;
+  return hp;
+}
+
+// Destinations each hop can have at most: seeds, then everything known so far, capped by the node
+// capacity and the graph.  False if a fanout takes whole neighbourhoods (no bound without degrees).
+bool hop_row_bounds(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t num_nodes, int64_t node_capacity,
+                    int64_t* rows /*[L]*/) {
+  int64_t n = num_seeds < num_nodes ? num_seeds : num_nodes;
+  for (int h = 0; h < L; ++h) {
+    if (fanouts[h] < 0) return false;
+    if (n > node_capacity) n = node_capacity;
+    rows[h] = n;
+    n = n + n * fanouts[h];
+    if (n > num_nodes) n = num_nodes;
+  }
+  return true;
+}
+
+// Whether every hop of a call can take the partition strategy; if so, what it needs of a workspace.
+bool part_needs(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t num_nodes, int64_t node_capacity,
+                int64_t* rec_entries, int64_t* hist_entries) {
+  int64_t rows[SMFG_MAX_LAYERS];
+  *rec_entries = 1;
+  *hist_entries = 1;
+  for (int h = 0; h < L; ++h)
+    if (fanouts[h] < 1 || fanouts[h] > SMFG_MAX_FANOUT) return false;
+  if (!hop_row_bounds(num_seeds, L, fanouts, num_nodes, node_capacity, rows)) return false;
+  for (int h = 0; h < L; ++h) {
+    const int64_t records = rows[h] * (1 + fanouts[h]);
+    if (records > kPartMaxRecords) return false;
+    const HopPlan hp = plan_hop(rows[h], fanouts[h]);
+    if (records > *rec_entries) *rec_entries = records;
+    if ((hp.row_blocks << hp.lgB) > *hist_entries) *hist_entries = hp.row_blocks << hp.lgB;
+  }
+  return true;
+}
+
+// The environment variable SMFG_DEDUP=table makes new workspaces use the table strategy even
+// where the partition strategy applies (for measuring one against the other).
+bool table_forced() {
+  const char* e = std::getenv("SMFG_DEDUP");
+  return e && std::strcmp(e, "table") == 0;
+}
+
 // Sizes of a workspace for up to max_seeds seeds, the given fanouts and capacities: fills every
 // field of *ws but the pointers (slab stays null).  Host only.
 int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, int32_t L, const int32_t* fanouts,
@@ -219,31 +289,47 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
   ws->node_capacity = node_capacity;
   ws->slot_entries = slots > 0 ? slots : 1;
   ws->table_log2 = lg;
+  ws->part = !table_forced() &&
+             part_needs(max_seeds, L, fanouts, g->num_nodes, node_capacity, &ws->rec_entries, &ws->hist_entries) &&
+             slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity) <= ws->slot_entries;
   const int64_t tiles = (node_capacity + kTileRows - 1) / kTileRows + 1;
-  ws->b_table = align256((int64_t(1) << lg) * 8);
   ws->b_slot = align256(ws->slot_entries * 4);
   ws->b_row = align256((node_capacity + 4) * 4);
   ws->b_tiles = align256(tiles * 8);
-  ws->b_stiles = align256((ws->slot_entries / kWideTile + 2) * 8);
-  ws->bytes = ws->b_table + 4 * ws->b_slot + 8 * ws->b_row + ws->b_tiles + ws->b_stiles;
+  if (ws->part) {
+    ws->b_rec = align256(ws->rec_entries * 8);
+    ws->b_hist = align256(ws->hist_entries * 4);
+    ws->b_bstart = align256((2 * (int64_t(1) << kPartMaxLgB) + 2) * 4);
+    ws->bytes = 2 * ws->b_slot + 4 * ws->b_row + ws->b_tiles + ws->b_rec + ws->b_hist + ws->b_bstart;
+  } else {
+    ws->b_table = align256((int64_t(1) << lg) * 8);
+    ws->b_stiles = align256((ws->slot_entries / kWideTile + 2) * 8);
+    ws->bytes = ws->b_table + 4 * ws->b_slot + 8 * ws->b_row + ws->b_tiles + ws->b_stiles;
+  }
   return SMFG_OK;
 }
 
 // Points the arrays of a planned workspace into `base` (ws->bytes bytes, 256-byte aligned).
 void bind_workspace(smfg_workspace* ws, void* base) {
   uint8_t* p = static_cast<uint8_t*>(base);
-  ws->table = reinterpret_cast<uint64_t*>(p); p += ws->b_table;
   ws->ent = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
-  ws->lostto = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
   ws->gsrc = reinterpret_cast<int32_t*>(p); p += ws->b_slot;
-  ws->rank = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
   ws->rowk = reinterpret_cast<int32_t*>(p); p += ws->b_row;
   ws->rowmn = reinterpret_cast<uint2*>(p); p += 2 * ws->b_row;
   ws->rowoff = reinterpret_cast<int32_t*>(p); p += ws->b_row;
+  ws->tile_sums = reinterpret_cast<uint64_t*>(p); p += ws->b_tiles;
+  if (ws->part) {
+    ws->rec = reinterpret_cast<uint64_t*>(p); p += ws->b_rec;
+    ws->hist = reinterpret_cast<uint32_t*>(p); p += ws->b_hist;
+    ws->bstart = reinterpret_cast<uint32_t*>(p);
+    return;
+  }
+  ws->table = reinterpret_cast<uint64_t*>(p); p += ws->b_table;
+  ws->lostto = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
+  ws->rank = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
   ws->rowstart = reinterpret_cast<int64_t*>(p); p += 2 * ws->b_row;
   ws->rowdeg = reinterpret_cast<int32_t*>(p); p += ws->b_row;
   p += ws->b_row;  // spare
-  ws->tile_sums = reinterpret_cast<uint64_t*>(p); p += ws->b_tiles;
   ws->stile_sums = reinterpret_cast<uint64_t*>(p);
 }
 
@@ -419,8 +505,8 @@ int smfg_workspace_create_sized(smfg_workspace_t** out, const smfg_graph_t* g, i
     return SMFG_ERR_OOM;
   }
   bind_workspace(ws, ws->slab);
-  // displacement notes start out clear; flag_rows clears whatever a call writes
-  e = hipMemset(ws->lostto, 0, static_cast<size_t>(ws->slot_entries) * 4);
+  // displacement notes (table strategy) start out clear; flag_rows clears whatever a call writes
+  e = ws->lostto ? hipMemset(ws->lostto, 0, static_cast<size_t>(ws->slot_entries) * 4) : hipSuccess;
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (cur != g->device) (void)hipSetDevice(cur);
   if (e != hipSuccess) {
@@ -524,6 +610,9 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     B.rowdeg = w->rowdeg;
     B.rank = w->rank;
     B.stile_sums = w->stile_sums;
+    B.rec = w->rec;
+    B.hist = w->hist;
+    B.bstart = w->bstart;
     B.features = static_cast<uint8_t*>(o.features);
     if (o.labels) {
       if (!g->labels) return SMFG_ERR_INVALID_ARG;
@@ -551,17 +640,42 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     }
   }
 
+  // Dedup strategy of the call: the partition strategy if every workspace was planned for it and
+  // the call's hops fit what they hold; the table strategy if every workspace holds a table.
+  bool part = true, table = true;
+  for (int b = 0; b < num_batches; ++b) {
+    part = part && ws[b]->part;
+    table = table && !ws[b]->part;
+  }
+  if (!part && !table) return SMFG_ERR_INVALID_ARG;  // workspaces of one call must be planned alike
+  HopPlan plan[SMFG_MAX_LAYERS];
+  if (part) {
+    if (wide) return SMFG_ERR_CAPACITY;  // such a workspace was planned for fanouts up to SMFG_MAX_FANOUT
+    for (int h = 0; h < L; ++h) {
+      plan[h] = plan_hop(max_n[h], fanouts[h]);
+      const int64_t records = max_n[h] * (1 + fanouts[h]);
+      for (int b = 0; b < num_batches; ++b)
+        if (records > ws[b]->rec_entries || (plan[h].row_blocks << plan[h].lgB) > ws[b]->hist_entries)
+          return SMFG_ERR_CAPACITY;
+    }
+  }
+
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   int cur = 0;
   (void)hipGetDevice(&cur);
   if (cur != g->device) (void)hipSetDevice(g->device);
   const unsigned G = static_cast<unsigned>(num_batches);
-  constexpr unsigned kCap = 4096;
+  constexpr unsigned kCap = 4096;  // blocks per batch of the grid-stride kernels
 
-  { StageTimer t_(SMFG_STAGE_CLEAR, st);
-  k_clear<<<dim3(blocks_for(int64_t(1) << max_table_log2, kThreads * 8, 2048), G), kThreads, 0, st>>>(P); }
-  { StageTimer t_(SMFG_STAGE_SEEDS, st);
-  k_insert_seeds<<<dim3(blocks_for(max_seeds, kThreads, kCap), G), kThreads, 0, st>>>(P); }
+  if (part) {
+    StageTimer t_(SMFG_STAGE_SEEDS, st);
+    k_begin<<<blocks_for(max_seeds, kThreads, kCap) * G, kThreads, 0, st>>>(P);
+  } else {
+    { StageTimer t_(SMFG_STAGE_CLEAR, st);
+    k_clear<<<blocks_for(int64_t(1) << max_table_log2, kThreads * 8, 2048) * G, kThreads, 0, st>>>(P); }
+    { StageTimer t_(SMFG_STAGE_SEEDS, st);
+    k_insert_seeds<<<blocks_for(max_seeds, kThreads, kCap) * G, kThreads, 0, st>>>(P); }
+  }
   for (int h = 0; h < L; ++h) {
     P.h = h;
     P.d = fanouts[h];
@@ -572,49 +686,82 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     }
     const int64_t rows = max_n[h];
     const unsigned tile_blocks = blocks_for(rows, kTileRows, kCap);
+    if (part) {
+      P.lgB = plan[h].lgB;
+      P.block_rows = plan[h].block_rows;
+      const unsigned row_blocks = static_cast<unsigned>(plan[h].row_blocks);
+      const unsigned buckets = 1u << P.lgB;
+      {
+        StageTimer t_(SMFG_STAGE_SAMPLE, st);
+        k_sample_hist<<<row_blocks * G, kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_PARTITION, st);
+        k_scan_hist<<<((buckets + kThreads - 1) / kThreads) * G, kThreads, 0, st>>>(P);
+        k_scatter<<<row_blocks * G, kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_DEDUP, st);
+        k_dedup_buckets<<<buckets * G, kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_FLAG, st);
+        k_flag_rows<false><<<tile_blocks * G, kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
+        k_scan_tiles<<<G, kThreads, 0, st>>>(P);
+      }
+      {
+        StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
+        k_assemble<false><<<tile_blocks * G, kThreads, 0, st>>>(P);
+      }
+      continue;
+    }
     if (wide) {
       int64_t samples = P.d < 0 ? max_entries : rows * P.d;  // upper bound of E_h
       if (samples > max_entries) samples = max_entries;
       const unsigned flat_blocks = blocks_for(samples, kWideTile, kCap);
       {
         StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
-        k_count_rows<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
-        k_scan_count_tiles<<<dim3(1, G), kThreads, 0, st>>>(P);
+        k_count_rows<<<tile_blocks * G, kThreads, 0, st>>>(P);
+        k_scan_count_tiles<<<G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_SAMPLE, st);
-        k_sample_insert_wide<<<dim3(blocks_for(rows, kThreads / 64, 2 * kCap), G), kThreads, 0, st>>>(P);
+        k_sample_insert_wide<<<blocks_for(rows, kThreads / 64, 2 * kCap) * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_FLAG, st);
-        k_flag_flat<<<dim3(flat_blocks, G), kThreads, 0, st>>>(P);
+        k_flag_flat<<<flat_blocks * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
-        k_scan_flat_tiles<<<dim3(1, G), kThreads, 0, st>>>(P);
+        k_scan_flat_tiles<<<G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
-        k_assemble_flat<<<dim3(flat_blocks, G), kThreads, 0, st>>>(P);
+        k_assemble_flat<<<flat_blocks * G, kThreads, 0, st>>>(P);
       }
       continue;
     }
     const unsigned row_blocks = blocks_for(rows, (64 / P.d) * (kThreads / 64), kCap);
     {
       StageTimer t_(SMFG_STAGE_SAMPLE, st);
-      k_sample_insert<<<dim3(row_blocks, G), kThreads, 0, st>>>(P);
+      k_sample_insert<<<row_blocks * G, kThreads, 0, st>>>(P);
     }
     {
       StageTimer t_(SMFG_STAGE_FLAG, st);
-      k_flag_rows<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
+      k_flag_rows<true><<<tile_blocks * G, kThreads, 0, st>>>(P);
     }
     {
       StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
-      k_scan_tiles<<<dim3(1, G), kThreads, 0, st>>>(P);
+      k_scan_tiles<<<G, kThreads, 0, st>>>(P);
     }
     {
       StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
-      k_assemble<<<dim3(tile_blocks, G), kThreads, 0, st>>>(P);
+      if (h == L - 1) k_assemble<false><<<tile_blocks * G, kThreads, 0, st>>>(P);
+      else k_assemble<true><<<tile_blocks * G, kThreads, 0, st>>>(P);
     }
   }
   if (want_feat) launch_gather(P, max_n[L], vb, G, st);
@@ -647,10 +794,13 @@ int smfg_sample_mfg_static(const smfg_graph_t* g, const int32_t* d_seeds, int32_
   rc = static_scratch_of(g->device, &base);
   if (rc == SMFG_OK) {
     bind_workspace(&ws, base);
-    // the array keeps what the last call left: the displacement notes must start out clear
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    k_fill_u32<<<blocks_for(ws.slot_entries, kThreads * 4, 1024), kThreads, 0, st>>>(ws.lostto, ws.slot_entries, 0u);
-    rc = hip_err(hipGetLastError());
+    // the array keeps what the last call left: the displacement notes of the table strategy must
+    // start out clear (nothing of the partition strategy's scratch is read before it is written)
+    if (ws.lostto) {
+      hipStream_t st = static_cast<hipStream_t>(hip_stream);
+      k_fill_u32<<<blocks_for(ws.slot_entries, kThreads * 4, 1024), kThreads, 0, st>>>(ws.lostto, ws.slot_entries, 0u);
+      rc = hip_err(hipGetLastError());
+    }
   }
   if (cur != g->device) (void)hipSetDevice(cur);
   if (rc != SMFG_OK) return rc;

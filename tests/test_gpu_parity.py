@@ -12,6 +12,18 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.fixture(autouse=True, params=["partition", "table"])
+def dedup_strategy(request, monkeypatch):
+    """Every test of this file runs with both dedup strategies of the fast path: the default (hash
+    partition, no global table) and the global table (what large hops and wide fanouts use), which
+    the environment variable SMFG_DEDUP=table selects for workspaces created while it is set."""
+    if request.param == "table":
+        monkeypatch.setenv("SMFG_DEDUP", "table")
+    else:
+        monkeypatch.delenv("SMFG_DEDUP", raising=False)
+    return request.param
+
+
 class GpuGraph:
     def __init__(self, indptr, indices, feat):
         self.h_indptr, self.h_indices, self.h_feat = indptr, indices, feat
@@ -593,6 +605,36 @@ def test_giant_hub_and_isolated_seeds():
             smfg.sample_mfg(gg.g, ws, torch.from_numpy(s).to(DEV), fan, 1234, out)
             assert_same(fetch(out, len(fan)), ref, len(fan))
     assert gg.oracle.sample_mfg(lonely, (5, 5), 1).num_edges == [0, 0]
+
+
+def test_partition_bucket_overflow_and_rounds(dedup_strategy):
+    """The partition strategy's per-bucket LDS table: 5000 distinct nodes whose hashes share their
+    12 leading bits all land in one of 1024 buckets and, on the first attempt, in one round of that
+    bucket, which overflows the 4096-slot table; the bucket must start over with more rounds and
+    still number every node exactly as the serial walk does.  Each of those nodes is sampled 12
+    times (60 000 single-neighbour destinations), so the rounds also see repeats."""
+    hash_mult = 0x9E3779B1            # the library's bucket hash is node * this mod 2^32, leading bits
+    n = 1 << 25
+    h = (np.arange(n, dtype=np.uint64) * np.uint64(hash_mult)) & np.uint64(0xFFFFFFFF)
+    special = np.nonzero((h >> np.uint64(20)) == np.uint64(0x5A3))[0][:5000]
+    assert len(special) == 5000
+    seeds = np.setdiff1d(np.arange(70_000), special)[:60_000].astype(np.int32)     # sorted
+    deg = np.zeros(n, dtype=np.int64)
+    deg[seeds] = 1
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(deg, out=indptr[1:])
+    indices = special[np.arange(len(seeds)) % len(special)].astype(np.int32)       # row of the j-th seed
+    gg = GpuGraph(indptr, indices, None)
+    rng = np.random.default_rng(5)
+    order = rng.permutation(len(seeds))
+    # the table strategy probes linearly from the same hash, so for it these ids are one long
+    # cluster: slow, still exact; a second hop makes the call too large for the partition strategy
+    for fan in [(32,), (32, 1)] if dedup_strategy == "partition" else [(32,)]:
+        s = seeds[order]
+        ref = gg.oracle.sample_mfg(s, fan, 77)
+        assert ref.num_nodes[1] == 65_000
+        res = run_one(gg, s, fan, 77)
+        assert_same(res, ref, len(fan))
 
 
 def test_single_node_graph():
