@@ -93,20 +93,51 @@ __global__ void __launch_bounds__(kThreads) k_sample_hist(const Launch P) {
   for (int b = threadIdx.x; b < nB; b += kThreads) out[b] = hist[b];
 }
 
-// One thread per bucket: counts of the bucket over the row blocks -> exclusive offsets; bucket size.
+// Counts of a bucket over the row blocks -> exclusive offsets, and the bucket's size.  A thread
+// block takes kScanCols buckets; kScanSegs threads share a bucket, each a contiguous range of the
+// row blocks (sum, then the ranges' exclusive scan in LDS, then the offsets).
+constexpr int kScanCols = 32;
+constexpr int kScanSegs = kThreads / kScanCols;
 __global__ void __launch_bounds__(kThreads) k_scan_hist(const Launch P) {
+  __shared__ uint32_t part[kScanSegs][kScanCols];
   const BatchCtx& B = P.b[batch_of_block(P)];
-  if (status_of(B, P.L) != 0) return;
+  if (block_has_status(B, P.L)) return;
   const int n = static_cast<int>(B.counts[P.h]);
   const int blocks = (n + P.block_rows - 1) / P.block_rows;
   const int nB = 1 << P.lgB;
-  const int b = block_in_batch(P) * kThreads + threadIdx.x;
+  const int c = threadIdx.x % kScanCols, seg = threadIdx.x / kScanCols;
+  const int b = block_in_batch(P) * kScanCols + c;
+  const int per = (blocks + kScanSegs - 1) / kScanSegs;
+  const int j0 = seg * per < blocks ? seg * per : blocks;
+  const int j1 = j0 + per < blocks ? j0 + per : blocks;
+  uint32_t* col = B.hist + (b < nB ? b : 0);
+  uint32_t sum = 0;
+  if (b < nB) {
+    int j = j0;
+    constexpr int U = 8;
+    for (; j + U <= j1; j += U) {
+      uint32_t t[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) t[u] = col[static_cast<size_t>(j + u) * nB];
+#pragma unroll
+      for (int u = 0; u < U; ++u) sum += t[u];
+    }
+    for (; j < j1; ++j) sum += col[static_cast<size_t>(j) * nB];
+  }
+  part[seg][c] = sum;
+  __syncthreads();
   if (b >= nB) return;
-  uint32_t run = 0;
-  uint32_t* col = B.hist + b;
-  int j = 0;
+  uint32_t run = 0, total = 0;
+#pragma unroll
+  for (int q = 0; q < kScanSegs; ++q) {
+    const uint32_t v = part[q][c];
+    if (q < seg) run += v;
+    total += v;
+  }
+  if (seg == 0) B.bstart[nB + 1 + b] = total;  // bucket size
+  int j = j0;
   constexpr int U = 8;
-  for (; j + U <= blocks; j += U) {
+  for (; j + U <= j1; j += U) {
     uint32_t t[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) t[u] = col[static_cast<size_t>(j + u) * nB];
@@ -116,17 +147,24 @@ __global__ void __launch_bounds__(kThreads) k_scan_hist(const Launch P) {
       run += t[u];
     }
   }
-  for (; j < blocks; ++j) {
+  for (; j < j1; ++j) {
     const uint32_t t = col[static_cast<size_t>(j) * nB];
     col[static_cast<size_t>(j) * nB] = run;
     run += t;
   }
-  B.bstart[nB + 1 + b] = run;  // bucket size
 }
 
-// Records of the block's destinations -> their buckets.
+// Records of the block's destinations -> their buckets.  The records of a round (up to
+// kScatterRound: the block's known nodes first, then its samples in position order) are counted
+// per bucket, ordered by bucket in LDS and written out in that order, so that the records a bucket
+// receives from this block leave as one run of consecutive addresses.
+constexpr int kScatterPer = 8;                          // stream elements per thread and round
+constexpr int kScatterRound = kScatterPer * kThreads;
 __global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
-  __shared__ uint32_t cur[1 << kPartMaxLgB];
+  __shared__ uint32_t gbase[1 << kPartMaxLgB];   // where this block's next record of a bucket goes
+  __shared__ uint32_t cnt[1 << kPartMaxLgB];     // records of the round per bucket
+  __shared__ uint32_t lstart[1 << kPartMaxLgB];  // their exclusive scan: first staging slot of a bucket
+  __shared__ unsigned long long stage[kScatterRound];
   __shared__ unsigned long long lds[kThreads / 64];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
@@ -136,9 +174,9 @@ __global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
   if (r0 >= n) return;
   const int r1 = r0 + P.block_rows < n ? r0 + P.block_rows : n;
   const int nB = 1 << P.lgB;
-  // first record of every bucket: exclusive scan of the bucket sizes, four buckets per thread
+  constexpr int per = (1 << kPartMaxLgB) / kThreads;  // buckets per thread in the scans
+  // first record of every bucket: exclusive scan of the bucket sizes
   {
-    constexpr int per = (1 << kPartMaxLgB) / kThreads;
     uint32_t sz[per];
     uint32_t mine = 0;
 #pragma unroll
@@ -154,47 +192,89 @@ __global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
     for (int u = 0; u < per; ++u) {
       const int b = threadIdx.x * per + u;
       if (b < nB) {
-        cur[b] = pre + offs[b];
+        gbase[b] = pre + offs[b];
         if (blk == 0) B.bstart[b] = pre;
       }
       pre += sz[u];
     }
     if (blk == 0 && threadIdx.x == 0) B.bstart[nB] = static_cast<uint32_t>(total);
   }
-  __syncthreads();
   const uint32_t d = static_cast<uint32_t>(P.d);
   const DivD div(d);
-  // known nodes: destination i has local id i
-  for (int i = r0 + threadIdx.x; i < r1; i += kThreads) {
-    const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
-    const uint32_t at = atomicAdd(&cur[part_bucket(v, P.lgB)], 1u);
-    B.rec[at] = (static_cast<unsigned long long>(v) << 32) | static_cast<uint32_t>(i);
-  }
-  // samples, flat over the padded positions of the block's destinations
+  const uint32_t known = static_cast<uint32_t>(r1 - r0);
   const uint32_t pos0 = static_cast<uint32_t>(r0) * d;
-  const uint32_t cnt = static_cast<uint32_t>(r1 - r0) * d;
-  constexpr int U = 4;
-  for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
-    uint32_t g[U], k[U], sl[U];
+  const uint32_t stream = known + known * d;  // known nodes, then the padded sample positions
+  for (uint32_t c0 = 0; c0 < stream; c0 += kScatterRound) {
+    __syncthreads();  // gbase complete / previous round written out
+    for (int b = threadIdx.x; b < nB; b += kThreads) cnt[b] = 0u;
+    __syncthreads();
+    unsigned long long rec[kScatterPer];
+    uint32_t k[kScatterPer], sl[kScatterPer], g[kScatterPer];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t idx = base + u * kThreads;
-      g[u] = 0u;
+    for (int u = 0; u < kScatterPer; ++u) {
+      const uint32_t e = c0 + u * kThreads + threadIdx.x;
       k[u] = 0u;
       sl[u] = 0u;
-      if (idx < cnt) {
+      g[u] = 0u;
+      if (e < known) {
+        g[u] = static_cast<uint32_t>(B.node_ids[r0 + static_cast<int>(e)]);
+        k[u] = 1u;
+      } else if (e < stream) {
         uint32_t r;
-        div.split(idx, r, sl[u]);
+        div.split(e - known, r, sl[u]);
         k[u] = static_cast<uint32_t>(B.rowk[r0 + static_cast<int>(r)]);
-        g[u] = static_cast<uint32_t>(B.gsrc[pos0 + idx]);
+        g[u] = static_cast<uint32_t>(B.gsrc[pos0 + (e - known)]);
       }
     }
+    uint32_t bk[kScatterPer], rk[kScatterPer];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t idx = base + u * kThreads;
-      if (idx < cnt && sl[u] < k[u]) {
-        const uint32_t at = atomicAdd(&cur[part_bucket(g[u], P.lgB)], 1u);
-        B.rec[at] = (static_cast<unsigned long long>(g[u]) << 32) | (kPend | (pos0 + idx));
+    for (int u = 0; u < kScatterPer; ++u) {
+      const uint32_t e = c0 + u * kThreads + threadIdx.x;
+      rec[u] = kEmpty;
+      bk[u] = 0u;
+      rk[u] = 0u;
+      if (e < stream && sl[u] < k[u]) {
+        // a known node (destination i has local id i), or a sample: tag | position
+        const uint32_t val = e < known ? static_cast<uint32_t>(r0) + e : (kPend | (pos0 + (e - known)));
+        rec[u] = (static_cast<unsigned long long>(g[u]) << 32) | val;
+        bk[u] = part_bucket(g[u], P.lgB);
+        rk[u] = atomicAdd(&cnt[bk[u]], 1u);
+      }
+    }
+    __syncthreads();
+    {
+      uint32_t c[per];
+      uint32_t mine = 0;
+#pragma unroll
+      for (int u = 0; u < per; ++u) {
+        const int b = threadIdx.x * per + u;
+        c[u] = b < nB ? cnt[b] : 0u;
+        mine += c[u];
+      }
+      unsigned long long total;
+      uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+#pragma unroll
+      for (int u = 0; u < per; ++u) {
+        const int b = threadIdx.x * per + u;
+        if (b < nB) lstart[b] = pre;
+        pre += c[u];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < kScatterPer; ++u)
+        if (rec[u] != kEmpty) stage[lstart[bk[u]] + rk[u]] = rec[u];
+      __syncthreads();
+      const uint32_t staged = static_cast<uint32_t>(total);
+      for (uint32_t t = threadIdx.x; t < staged; t += kThreads) {
+        const unsigned long long r = stage[t];
+        const uint32_t b = part_bucket(static_cast<uint32_t>(r >> 32), P.lgB);
+        B.rec[gbase[b] + (t - lstart[b])] = r;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < per; ++u) {
+        const int b = threadIdx.x * per + u;
+        if (b < nB) gbase[b] += c[u];
       }
     }
   }
@@ -230,55 +310,75 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
       for (uint32_t q = threadIdx.x; q < kPartSlots; q += kThreads) tab[q] = kEmpty;
       if (threadIdx.x == 0) overflow_lds = 0;
       __syncthreads();
-      for (uint32_t r = rec0 + threadIdx.x; r < rec1; r += kThreads) {
-        const unsigned long long mine = B.rec[r];
-        const uint32_t node = static_cast<uint32_t>(mine >> 32);
-        const uint32_t hsh = node * kPartHash;
-        if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
-        uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
-        uint32_t probes = 0;
-        for (; probes < kPartSlots; ++probes) {
-          const unsigned long long old = atomicCAS(&tab[sl], kEmpty, mine);
-          if (old == kEmpty) break;
-          if (static_cast<uint32_t>(old >> 32) == node) {
-            if (old > mine) atomicMin(&tab[sl], mine);
-            break;
-          }
-          sl = (sl + 1u) & (kPartSlots - 1u);
+      constexpr int U = 8;  // records in flight per thread
+      for (uint32_t c0 = rec0; c0 < rec1; c0 += kThreads * U) {
+        unsigned long long mine[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const uint32_t r = c0 + u * kThreads + threadIdx.x;
+          mine[u] = r < rec1 ? B.rec[r] : kEmpty;
         }
-        if (probes == kPartSlots) overflow_lds = 1;
-      }
-      __syncthreads();
-      failed = overflow_lds != 0;
-      if (!failed) {
-        for (uint32_t r = rec0 + threadIdx.x; r < rec1; r += kThreads) {
-          const unsigned long long mine = B.rec[r];
-          const uint32_t node = static_cast<uint32_t>(mine >> 32);
-          const uint32_t val = static_cast<uint32_t>(mine);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (mine[u] == kEmpty) continue;
+          const uint32_t node = static_cast<uint32_t>(mine[u] >> 32);
           const uint32_t hsh = node * kPartHash;
           if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
           uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
-          uint32_t least = 0u;
           uint32_t probes = 0;
           for (; probes < kPartSlots; ++probes) {
-            const unsigned long long t = tab[sl];
-            if (static_cast<uint32_t>(t >> 32) == node) {
-              least = static_cast<uint32_t>(t);
+            const unsigned long long old = atomicCAS(&tab[sl], kEmpty, mine[u]);
+            if (old == kEmpty) break;
+            if (static_cast<uint32_t>(old >> 32) == node) {
+              if (old > mine[u]) atomicMin(&tab[sl], mine[u]);
               break;
             }
             sl = (sl + 1u) & (kPartSlots - 1u);
           }
-          if (probes == kPartSlots) {  // every inserted node is found again
-            set_status(B, P.L, SMFG_ST_INTERNAL);
-            continue;
+          if (probes == kPartSlots) overflow_lds = 1;
+        }
+      }
+      __syncthreads();
+      failed = overflow_lds != 0;
+      if (!failed) {
+        constexpr int U = 8;
+        for (uint32_t c0 = rec0; c0 < rec1; c0 += kThreads * U) {
+          unsigned long long mine[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const uint32_t r = c0 + u * kThreads + threadIdx.x;
+            mine[u] = r < rec1 ? B.rec[r] : kEmpty;
           }
-          if (val < kPend) {
-            // a known node: two of them with one id can only be a repeated seed
-            if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
-          } else {
-            // least < kPend: the node's final local id; least == val: this sample is the node's
-            // first appearance; else least names the position of the first appearance
-            B.ent[val & ~kTagMask] = least == val ? kSlot : least;
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            if (mine[u] == kEmpty) continue;
+            const uint32_t node = static_cast<uint32_t>(mine[u] >> 32);
+            const uint32_t val = static_cast<uint32_t>(mine[u]);
+            const uint32_t hsh = node * kPartHash;
+            if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
+            uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
+            uint32_t least = 0u;
+            uint32_t probes = 0;
+            for (; probes < kPartSlots; ++probes) {
+              const unsigned long long t = tab[sl];
+              if (static_cast<uint32_t>(t >> 32) == node) {
+                least = static_cast<uint32_t>(t);
+                break;
+              }
+              sl = (sl + 1u) & (kPartSlots - 1u);
+            }
+            if (probes == kPartSlots) {  // every inserted node is found again
+              set_status(B, P.L, SMFG_ST_INTERNAL);
+              continue;
+            }
+            if (val < kPend) {
+              // a known node: two of them with one id can only be a repeated seed
+              if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
+            } else {
+              // least < kPend: the node's final local id; least == val: this sample is the node's
+              // first appearance; else least names the position of the first appearance
+              B.ent[val & ~kTagMask] = least == val ? kSlot : least;
+            }
           }
         }
       }

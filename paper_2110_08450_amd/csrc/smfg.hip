@@ -697,7 +697,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       }
       {
         StageTimer t_(SMFG_STAGE_PARTITION, st);
-        k_scan_hist<<<((buckets + kThreads - 1) / kThreads) * G, kThreads, 0, st>>>(P);
+        k_scan_hist<<<((buckets + kScanCols - 1) / kScanCols) * G, kThreads, 0, st>>>(P);
         k_scatter<<<row_blocks * G, kThreads, 0, st>>>(P);
       }
       {
