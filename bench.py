@@ -109,6 +109,8 @@ def main():
                          "buffer sets); 0: every launch set runs start to end on one stream (see --streams)")
     ap.add_argument("--feat-dim", type=int, default=0, help="experiment: override the feature width")
     ap.add_argument("--depth", type=int, default=2, help="buffer sets of the pipelined run")
+    ap.add_argument("--sample-streams", type=int, default=1,
+                    help="pipelined run: launch sets alternate over this many sampling streams (needs depth > streams)")
     ap.add_argument("--row-stride", type=int, default=0,
                     help="experiment: feature row stride in bytes (>= row bytes; 0 = dense rows)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
@@ -162,7 +164,7 @@ def main():
     if args.pipeline:
         from paper_2110_08450_amd.pipeline import BatchPipeline
         pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G, sample_capacity=scap,
-                             depth=max(2, args.depth))
+                             depth=max(2, args.depth, args.sample_streams + 1), sample_streams=args.sample_streams)
         S, streams, wss, outs = 2, [pipe.s_sample, pipe.s_gather], pipe.wss, pipe.outs
     else:
         S = max(1, args.streams)

@@ -11,13 +11,15 @@
 //   scatter       moves the records into their buckets (one contiguous range of `rec` each);
 //   dedup_buckets one block per bucket builds a hash table of the bucket's nodes in LDS, keeping
 //                 the smallest value per node (a known node's local id always wins, else the
-//                 earliest scan position), then writes every sample's state into ent[position]:
-//                 the final local id (known node), "first appearance", or the position of the
-//                 first appearance.
-// flag_rows / scan_tiles / assemble then number the first appearances in scan order, exactly the
-// ids the serial first-encounter rule gives.  Which thread inserts first never matters: only
-// minima are kept.  All global traffic but the neighbour reads and the scattered 4-byte state
-// writes is streaming, and there are no global atomics.
+//                 earliest scan position).  A sample that is its node's first appearance keeps
+//                 its gsrc entry (the node id, bit 31 clear); every other sample's entry is
+//                 overwritten with kResolved | final local id (known node) or kPointer | position
+//                 of the first appearance.  In the outer hops most samples are first appearances,
+//                 so few entries are rewritten.
+// flag_rows_part / scan_tiles / assemble_part then number the first appearances in scan order,
+// exactly the ids the serial first-encounter rule gives.  Which thread inserts first never
+// matters: only minima are kept.  All global traffic but the neighbour reads and those scattered
+// 4-byte rewrites is streaming, and there are no global atomics.
 #ifndef SMFG_KERNELS_PART_H_
 #define SMFG_KERNELS_PART_H_
 
@@ -33,6 +35,8 @@ constexpr int kPartBucketRecords = 2048;            // buckets are sized for at 
 constexpr int64_t kPartMaxRecords = static_cast<int64_t>(kPartBucketRecords) << kPartMaxLgB;
 constexpr int kPartMaxRowBlocks = 512;              // row blocks per batch and hop (plus a ragged one)
 constexpr uint32_t kPartHash = 0x9E3779B1u;         // odd: node -> node * kPartHash is a bijection on 32 bits
+constexpr uint32_t kResolved = 0x80000000u;         // gsrc entry: low 30 bits = final local id of a known node
+constexpr uint32_t kPointer = 0xC0000000u;          // gsrc entry: low 30 bits = position of the first appearance
 
 __device__ __forceinline__ uint32_t part_bucket(uint32_t node, int lgB) {
   return lgB == 0 ? 0u : (node * kPartHash) >> (32 - lgB);
@@ -376,8 +380,10 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
               if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
             } else {
               // least < kPend: the node's final local id; least == val: this sample is the node's
-              // first appearance; else least names the position of the first appearance
-              B.ent[val & ~kTagMask] = least == val ? kSlot : least;
+              // first appearance (entry stays); else least names the position of the first appearance
+              if (least != val)
+                B.gsrc[val & ~kTagMask] = static_cast<int32_t>(least < kPend ? (kResolved | least)
+                                                                             : (kPointer | (least & ~kTagMask)));
             }
           }
         }
@@ -390,6 +396,151 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
       break;
     }
     ++lgR;
+  }
+}
+
+// flag_rows for the entries dedup_buckets leaves: a valid sample whose entry still is a node id
+// (bit 31 clear) is a first appearance.  Per destination: bit mask of its first appearances; in-tile
+// exclusive scan of (samples, new nodes); per-tile totals.
+__global__ void __launch_bounds__(kThreads) k_flag_rows_part(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  __shared__ int k_lds[kTileRows];
+  __shared__ unsigned int mask_lds[kTileRows];
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const int nblocks = blocks_per_batch(P);
+  const int n = static_cast<int>(B.counts[P.h]);
+  const uint32_t d = static_cast<uint32_t>(P.d);
+  const DivD div(d);
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  for (int tile = block_in_batch(P); tile < tiles; tile += nblocks) {
+    const int i0 = tile * kTileRows;
+    const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
+    const int tr = threadIdx.x;
+    __syncthreads();
+    k_lds[tr] = tr < nrows ? B.rowk[i0 + tr] : 0;
+    mask_lds[tr] = 0u;
+    __syncthreads();
+    const uint32_t pos0 = static_cast<uint32_t>(i0) * d;
+    const uint32_t cnt = static_cast<uint32_t>(nrows) * d;
+    constexpr int U = 4;
+    for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
+      uint32_t e[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        e[u] = idx < cnt ? static_cast<uint32_t>(B.gsrc[pos0 + idx]) : kResolved;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        if (idx < cnt && (e[u] & kResolved) == 0u) {
+          uint32_t r, sl;
+          div.split(idx, r, sl);
+          if (sl < static_cast<uint32_t>(k_lds[r])) atomicOr(&mask_lds[r], 1u << sl);
+        }
+      }
+    }
+    __syncthreads();
+    const int k = k_lds[tr];
+    const uint32_t m = mask_lds[tr];
+    const unsigned long long x = (static_cast<unsigned long long>(k) << 32) | static_cast<unsigned long long>(__popc(m));
+    unsigned long long total;
+    const unsigned long long pre = block_exscan(x, lds, total);
+    if (tr < nrows) {
+      B.rowmn[i0 + tr] = make_uint2(m, static_cast<uint32_t>(pre & 0xFFFFFFFFull));
+      B.rowoff[i0 + tr] = static_cast<int32_t>(pre >> 32);
+    }
+    if (tr == 0) B.tile_sums[tile] = total;
+  }
+}
+
+// assemble for those entries: block indptr; block indices = final local ids; node ids of the
+// first appearances.  A pointer always names a first appearance, so one lookup of that
+// destination's record settles it.
+__global__ void __launch_bounds__(kThreads) k_assemble_part(const Launch P) {
+  __shared__ int k_lds[kTileRows];
+  __shared__ unsigned int mask_lds[kTileRows];
+  __shared__ unsigned int off_lds[kTileRows];   // global edge offset of the destination
+  __shared__ unsigned int rank_lds[kTileRows];  // local id of the destination's first new node
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const int n = static_cast<int>(B.counts[P.h]);
+  const uint32_t d = static_cast<uint32_t>(P.d);
+  const DivD div(d);
+  const int tiles = (n + kTileRows - 1) / kTileRows;
+  const int nblocks = blocks_per_batch(P);
+  for (int tile = block_in_batch(P); tile < tiles; tile += nblocks) {
+    const int i0 = tile * kTileRows;
+    const int nrows = n - i0 < kTileRows ? n - i0 : kTileRows;
+    const int tr = threadIdx.x;
+    const unsigned long long tpre = B.tile_sums[tile];
+    __syncthreads();
+    if (tr < nrows) {
+      const uint32_t off = static_cast<uint32_t>(tpre >> 32) + static_cast<uint32_t>(B.rowoff[i0 + tr]);
+      const uint2 mn = B.rowmn[i0 + tr];
+      k_lds[tr] = B.rowk[i0 + tr];
+      mask_lds[tr] = mn.x;
+      off_lds[tr] = off;
+      rank_lds[tr] = static_cast<uint32_t>(n) + static_cast<uint32_t>(tpre & 0xFFFFFFFFull) + mn.y;
+      B.blk_indptr[i0 + tr] = static_cast<int32_t>(off);
+    } else {
+      k_lds[tr] = 0;
+    }
+    __syncthreads();
+    const uint32_t pos0 = static_cast<uint32_t>(i0) * d;
+    const uint32_t cnt = static_cast<uint32_t>(nrows) * d;
+    constexpr int U = 4;
+    for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * U) {
+      uint32_t e[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        e[u] = idx < cnt ? static_cast<uint32_t>(B.gsrc[pos0 + idx]) : 0u;
+      }
+      // the records of the destinations that pointers name are fetched for all U samples of the
+      // thread before any is used (other samples fetch the tile's first record), so the scattered
+      // reads of a thread overlap
+      uint32_t r[U], sl[U], q[U], qi[U];
+      bool live[U], dup[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t idx = base + u * kThreads;
+        r[u] = 0u;
+        sl[u] = 0u;
+        if (idx < cnt) div.split(idx, r[u], sl[u]);
+        live[u] = idx < cnt && sl[u] < static_cast<uint32_t>(k_lds[r[u]]);
+        dup[u] = live[u] && (e[u] & kPointer) == kPointer;
+        q[u] = dup[u] ? (e[u] & ~kPointer) : pos0;
+        qi[u] = q[u] / d;
+      }
+      uint2 mn[U];
+      uint32_t ts[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        mn[u] = B.rowmn[qi[u]];
+        ts[u] = static_cast<uint32_t>(B.tile_sums[qi[u] / kTileRows] & 0xFFFFFFFFull);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
+        uint32_t local;
+        if ((e[u] & kResolved) == 0u) {  // first appearance: rank among the new nodes of this hop
+          local = rank_lds[r[u]] + __popc(mask_lds[r[u]] & ((1u << sl[u]) - 1u));
+          B.node_ids[local] = static_cast<int32_t>(e[u]);
+        } else if (dup[u]) {
+          const uint32_t qs = q[u] - qi[u] * d;
+          local = static_cast<uint32_t>(n) + ts[u] + mn[u].y + __popc(mn[u].x & ((1u << qs) - 1u));
+          if (((mn[u].x >> qs) & 1u) == 0u) {  // the named sample is not a first appearance: scratch disturbed
+            set_status(B, P.L, SMFG_ST_INTERNAL);
+            local = 0u;
+          }
+        } else {
+          local = e[u] & ~kPointer;
+        }
+        B.blk_indices[off_lds[r[u]] + sl[u]] = static_cast<int32_t>(local);
+      }
+    }
   }
 }
 

@@ -300,7 +300,7 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
     ws->b_rec = align256(ws->rec_entries * 8);
     ws->b_hist = align256(ws->hist_entries * 4);
     ws->b_bstart = align256((2 * (int64_t(1) << kPartMaxLgB) + 2) * 4);
-    ws->bytes = 2 * ws->b_slot + 4 * ws->b_row + ws->b_tiles + ws->b_rec + ws->b_hist + ws->b_bstart;
+    ws->bytes = ws->b_slot + 4 * ws->b_row + ws->b_tiles + ws->b_rec + ws->b_hist + ws->b_bstart;
   } else {
     ws->b_table = align256((int64_t(1) << lg) * 8);
     ws->b_stiles = align256((ws->slot_entries / kWideTile + 2) * 8);
@@ -312,7 +312,6 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
 // Points the arrays of a planned workspace into `base` (ws->bytes bytes, 256-byte aligned).
 void bind_workspace(smfg_workspace* ws, void* base) {
   uint8_t* p = static_cast<uint8_t*>(base);
-  ws->ent = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
   ws->gsrc = reinterpret_cast<int32_t*>(p); p += ws->b_slot;
   ws->rowk = reinterpret_cast<int32_t*>(p); p += ws->b_row;
   ws->rowmn = reinterpret_cast<uint2*>(p); p += 2 * ws->b_row;
@@ -325,6 +324,7 @@ void bind_workspace(smfg_workspace* ws, void* base) {
     return;
   }
   ws->table = reinterpret_cast<uint64_t*>(p); p += ws->b_table;
+  ws->ent = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
   ws->lostto = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
   ws->rank = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
   ws->rowstart = reinterpret_cast<int64_t*>(p); p += 2 * ws->b_row;
@@ -706,7 +706,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       }
       {
         StageTimer t_(SMFG_STAGE_FLAG, st);
-        k_flag_rows<false><<<tile_blocks * G, kThreads, 0, st>>>(P);
+        k_flag_rows_part<<<tile_blocks * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
@@ -714,7 +714,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       }
       {
         StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
-        k_assemble<false><<<tile_blocks * G, kThreads, 0, st>>>(P);
+        k_assemble_part<<<tile_blocks * G, kThreads, 0, st>>>(P);
       }
       continue;
     }

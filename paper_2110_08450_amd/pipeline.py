@@ -18,7 +18,8 @@ from . import binding as smfg
 
 class BatchPipeline:
     def __init__(self, g: smfg.Graph, fanouts: Sequence[int], batch_size: int, batches_per_set: int = 8,
-                 node_capacity: Optional[int] = None, depth: int = 2, sample_capacity: int = 0):
+                 node_capacity: Optional[int] = None, depth: int = 2, sample_capacity: int = 0,
+                 sample_streams: int = 1):
         self.g, self.fanouts = g, tuple(fanouts)
         self.G = max(1, min(batches_per_set, smfg.MAX_BATCHES))
         self.depth = depth
@@ -27,8 +28,12 @@ class BatchPipeline:
                     for _ in range(depth)]
         self.outs = [[smfg.alloc_output(g, batch_size, self.fanouts, node_capacity) for _ in range(self.G)]
                      for _ in range(depth)]
-        self.s_sample = torch.cuda.Stream()
+        # launch sets alternate over the sampling streams, so that the short kernels of one set's
+        # first hops can fill the gaps of another set's (depth must exceed their number)
+        self.s_samples = [torch.cuda.Stream() for _ in range(max(1, min(sample_streams, depth - 1)))]
+        self.s_sample = self.s_samples[0]
         self.s_gather = torch.cuda.Stream()
+        self._issued = 0
         self.sampled = [torch.cuda.Event() for _ in range(depth)]
         self.gathered = [torch.cuda.Event() for _ in range(depth)]
         self.released = [torch.cuda.Event() for _ in range(depth)]   # consumer is done with the set
@@ -40,17 +45,19 @@ class BatchPipeline:
         outs = self.outs[q][:k]
         if before_launch is not None:
             before_launch(outs)
-        self.s_sample.wait_event(self.released[q])
-        self.s_sample.wait_event(self.gathered[q])
-        smfg.sample_mfg_many(self.g, self.wss[q][:k], seeds, self.fanouts, keys, outs, stream=self.s_sample,
+        ss = self.s_samples[self._issued % len(self.s_samples)]
+        self._issued += 1
+        ss.wait_event(self.released[q])
+        ss.wait_event(self.gathered[q])
+        smfg.sample_mfg_many(self.g, self.wss[q][:k], seeds, self.fanouts, keys, outs, stream=ss,
                              with_features=self.g.feat is None)
-        self.sampled[q].record(self.s_sample)
+        self.sampled[q].record(ss)
         if self.g.feat is not None:
             self.s_gather.wait_event(self.sampled[q])
             smfg.gather_many(self.g, outs, stream=self.s_gather)
             self.gathered[q].record(self.s_gather)
         else:
-            self.gathered[q].record(self.s_sample)
+            self.gathered[q].record(ss)
         return outs
 
     def run(self, seed_batches: Sequence[torch.Tensor], rng_keys: Sequence[int]) -> Iterator[List[smfg.Output]]:
@@ -62,7 +69,8 @@ class BatchPipeline:
         # inputs must be complete before the side streams read them
         start = torch.cuda.Event()
         start.record(torch.cuda.current_stream())
-        self.s_sample.wait_event(start)
+        for ss in self.s_samples:
+            ss.wait_event(start)
         pending = []
         nxt = 0
         while nxt < len(sets) and len(pending) < self.depth:
