@@ -26,11 +26,89 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 
-# HBM bytes per k_gather launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (profiles/*_kernel_trace_and_hbm_traffic.txt), scaled by what the same counters read
-# for the identity copy of known size; keyed by (workload, batches per launch).
-MEASURED_GATHER_TRAFFIC_BYTES = {("papers", 8): 3.610e9, ("large", 8): 2.414e9}
+
+def source_hash():
+    """sha256 over the library's sources (kernels, host side, header): names the code a stored
+    counter figure was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2110_08450_amd", "csrc")
+    files = sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "smfg.h")]
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic(workload, batches_per_call):
+    """HBM bytes per k_gather launch from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of
+    this command, as `bench.py --traffic-from` stored them in profiles/traffic.json; None with a
+    note if there is no entry, or if it was measured on other sources than the ones present."""
+    try:
+        table = json.load(open(TRAFFIC_JSON))
+    except (OSError, ValueError):
+        return None, "no profiles/traffic.json"
+    e = table.get(f"{workload}/{batches_per_call}")
+    if e is None:
+        return None, f"profiles/traffic.json has no entry for {workload}/{batches_per_call}"
+    if e.get("source_hash") != source_hash():
+        return None, (f"profiles/traffic.json entry for {workload}/{batches_per_call} was measured on sources "
+                      f"{e.get('source_hash')}, present sources are {source_hash()}: not reported")
+    return e["gather_bytes_per_row"], (f"stored figure from rocprofv3 --pmc runs of this command on these sources "
+                                          f"(FETCH_SIZE x {e['fetch_scale']:.3f} + WRITE_SIZE x {e['write_scale']:.3f}, "
+                                          f"scales from the identity copy of known size)")
+
+
+def traffic_from(fetch_csv, write_csv, bench_json):
+    """Reads the counter_collection csv files of `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
+    runs of `bench.py --calibrate ...` and the JSON line one of those runs printed, scales both
+    counters by what they read for the identity gather of known size (k_gather_plain, launched by
+    --calibrate) and stores the k_gather figure per gathered row."""
+    line = [ln for ln in open(bench_json) if ln.startswith('{"metric"')][-1]
+    res = json.loads(line)
+    workload = res["config"]["workload"].split(":")[0]
+    batches_per_call = res["config"]["batches_per_call"]
+    rows_per_launch = res["config"]["mean_nodes_per_batch"] * batches_per_call
+    import csv
+    import re
+
+    def per_kernel(path, counter):
+        acc = {}
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != counter:
+                continue
+            m = re.search(r"(k_gather_plain|k_gather)\b", r["Kernel_Name"])
+            if m:
+                acc.setdefault(m.group(1), []).append((float(r["Counter_Value"]), int(r["Grid_Size"])))
+        return acc
+    fe, wr = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
+    # the identity gather: grid = ceil(rows / 32) blocks of 256 threads, rows x row_bytes in and out (+ 4 B ids in)
+    import torch  # noqa: F401  (only for the workload table's dtypes)
+    from paper_2110_08450_amd import synth
+    w = synth.WORKLOADS[workload]
+    row_bytes = w.feat_dim * (2 if "16" in str(w.feat_dtype) else 4)
+    (f_plain, grid), (w_plain, _) = fe["k_gather_plain"][0], wr["k_gather_plain"][0]
+    rows = min((1 << 30) // row_bytes, w.num_nodes)
+    assert (rows + 31) // 32 * 256 == grid, "the calibration launch is not the identity gather this expects"
+    fetch_scale = (rows * (row_bytes + 4) / 1024.0) / f_plain
+    write_scale = (rows * row_bytes / 1024.0) / w_plain
+    # timed-region launches only: the largest grids are the full launch sets
+    full = max(g for _, g in fe["k_gather"])
+    f_mean = sum(v for v, g in fe["k_gather"] if g == full) / sum(1 for _, g in fe["k_gather"] if g == full)
+    w_mean = sum(v for v, g in wr["k_gather"] if g == full) / sum(1 for _, g in wr["k_gather"] if g == full)
+    try:
+        table = json.load(open(TRAFFIC_JSON))
+    except (OSError, ValueError):
+        table = {}
+    table[f"{workload}/{batches_per_call}"] = {
+        "gather_bytes_per_row": (f_mean * fetch_scale + w_mean * write_scale) * 1024.0 / rows_per_launch,
+        "rows_per_full_launch": rows_per_launch,
+        "fetch_KiB": f_mean, "write_KiB": w_mean, "fetch_scale": fetch_scale, "write_scale": write_scale,
+        "source_hash": source_hash()}
+    json.dump(table, open(TRAFFIC_JSON, "w"), indent=1, sort_keys=True)
+    print(json.dumps(table[f"{workload}/{batches_per_call}"]))
 
 
 def log(*a):
@@ -113,8 +191,11 @@ def main():
                     help="pipelined run: launch sets alternate over this many sampling streams (needs depth > streams)")
     ap.add_argument("--row-stride", type=int, default=0,
                     help="experiment: feature row stride in bytes (>= row bytes; 0 = dense rows)")
+    ap.add_argument("--passes", type=int, default=0,
+                    help="timed passes of --steps batches each (0 = at least 5, more until about 0.6 s are timed)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="oracle time budget per host thread")
-    ap.add_argument("--cpu-threads", type=int, default=0, help="0 = min(16, cores available)")
+    ap.add_argument("--cpu-threads", type=int, default=0,
+                    help="0 = the CPU share the harness reports (OMP_NUM_THREADS if set, else the affinity mask)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--stages", action="store_true", help="extra untimed pass with every launch timed")
     ap.add_argument("--consume", action="store_true",
@@ -122,7 +203,14 @@ def main():
                          "on every prepared batch while the next launch set is being prepared")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run plain copies of known size (1 GiB in, 1 GiB out) for counter calibration")
+    ap.add_argument("--traffic-from", nargs=3, metavar=("FETCH_CSV", "WRITE_CSV", "BENCH_LOG"),
+                    help="no benchmark: store the k_gather HBM traffic of two rocprofv3 --pmc runs (FETCH_SIZE, "
+                         "WRITE_SIZE counter_collection csv files) of `bench.py --calibrate` and the log holding "
+                         "that run's JSON line into profiles/traffic.json")
     args = ap.parse_args()
+    if args.traffic_from:
+        traffic_from(*args.traffic_from)
+        return
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (batches are independent, so more GPUs would each "
             "take their own batches of a replicated graph); run with --gpus 1")
@@ -173,71 +261,108 @@ def main():
         outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
     row_bytes = g.row_bytes
 
-    K = max(1, args.steps)      # exactly K timed batches; the last launch set may be partial
+    K = max(1, args.steps)      # a pass = exactly K batches; its last launch set may be partial
     W = max(0, args.warmup)
     keys = [synth.batch_rng_key(w, i) for i in range(len(batches))]
-    counts_all = torch.zeros((K + W, 2 * L + 2), dtype=torch.int64, device=dev)
-    stride = counts_all.stride(0) * 8
+    depth = pipe.depth if pipe is not None else S
+    # Per-batch counts live in a ring of rows: a buffer set is reused `depth` launch sets later (the
+    # pipeline's events order that), a ring slot one launch set after that.
+    ring = depth + 1
+    counts_ring = torch.zeros((ring * G, 2 * L + 2), dtype=torch.int64, device=dev)
+    stride = counts_ring.stride(0) * 8
 
-    last_call = {}   # buffer set -> (first batch index, batches) of the last launch set that used it
+    last_call = {}   # buffer set -> (first batch index, batches, ring slot) of the last launch set that used it
     sets_issued = [0]
 
-    def run_pipelined(first, n):
-        for c in range(first, first + n, G):
-            k = min(G, first + n - c)
-            q = sets_issued[0] % pipe.depth
-            sets_issued[0] += 1
-            last_call[q] = (c, k)
-            idx = [(c + b) % len(batches) for b in range(k)]
-
-            def point_counts(os_, c=c):
-                for b, o in enumerate(os_):
-                    o.c.counts = counts_all.data_ptr() + (c + b) * stride
-            pipe.issue(q, [batches[i] for i in idx], [keys[i] for i in idx], before_launch=point_counts)
-
     def run_calls(first, n):
-        if args.pipeline:
-            return run_pipelined(first, n)
+        """Issues batches first .. first+n-1 (indices modulo the number of seed batches)."""
         for c in range(first, first + n, G):
             k = min(G, first + n - c)
-            q = sets_issued[0] % S
+            s_no = sets_issued[0]
             sets_issued[0] += 1
-            last_call[q] = (c, k)
+            q = s_no % depth
+            slot = s_no % ring
+            last_call[q] = (c, k, slot)
             idx = [(c + b) % len(batches) for b in range(k)]
-            for b in range(k):
-                outs[q][b].c.counts = counts_all.data_ptr() + (c + b) * stride
-            smfg.sample_mfg_many(g, wss[q][:k], [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx],
-                                 outs[q][:k], stream=streams[q])
+            base = counts_ring.data_ptr() + slot * G * stride
+            if pipe is not None:
+                def point_counts(os_, base=base):
+                    for b, o in enumerate(os_):
+                        o.c.counts = base + b * stride
+                pipe.issue(q, [batches[i] for i in idx], [keys[i] for i in idx], before_launch=point_counts)
+            else:
+                for b in range(k):
+                    outs[q][b].c.counts = base + b * stride
+                smfg.sample_mfg_many(g, wss[q][:k], [batches[i] for i in idx], w.fanouts, [keys[i] for i in idx],
+                                     outs[q][:k], stream=streams[q])
 
-    run_calls(0, W)
-    torch.cuda.synchronize()
-    smfg.profile_begin(1, K // G + 2)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_calls(W, K)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    stages = smfg.profile_end()
-
-    cnt = counts_all[W:].cpu().tolist()
-    assert all(c[2 * L + 1] == 0 for c in cnt), "a timed batch reported a device status"
+    # Accounting pass (untimed, also the first warm-up): the K batches of a pass, launch set by
+    # launch set with a synchronisation after each, to read their sizes.
+    cnt = []
+    for c in range(0, K, G):
+        k = min(G, K - c)
+        run_calls(c, k)
+        torch.cuda.synchronize()
+        slot = (sets_issued[0] - 1) % ring
+        cnt += counts_ring[slot * G:slot * G + k].cpu().tolist()
+    assert all(c[2 * L + 1] == 0 for c in cnt), "a batch reported a device status"
     n_final = sum(c[L] for c in cnt)
     edges = sum(sum(c[L + 1:2 * L + 1]) for c in cnt)
     alg = sum(algorithmic_bytes(c[:L + 1], c[L + 1:2 * L + 1], row_bytes) for c in cnt)
+
+    # Warm-up as asked, but never less than `depth` full launch sets, then one probe pass to size
+    # the number of timed passes.
+    warm = max(W, depth * G)
+    run_calls(K, warm)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_calls(0, K)
+    torch.cuda.synchronize()
+    probe = time.perf_counter() - t0
+    passes = args.passes if args.passes > 0 else int(min(max(5, 0.6 / max(probe, 1e-6)), 400, max(5, 30.0 / max(probe, 1e-6))))
+    sets_per_pass = (K + G - 1) // G
+
+    # Timed region: `passes` passes of K batches each, issued back to back (no host synchronisation
+    # between them), bracketed by device synchronisations.  A pass ends when the last stream has
+    # finished its work of that pass: events on every stream after each pass, all measured from one
+    # start event.
+    ev_start = torch.cuda.Event(enable_timing=True)
+    ev_end = [[torch.cuda.Event(enable_timing=True) for _ in streams] for _ in range(passes)]
+    smfg.profile_begin(1, passes * sets_per_pass + 2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    ev_start.record(streams[0])
+    for st in streams[1:]:
+        st.wait_event(ev_start)
+    for p_ in range(passes):
+        run_calls(0, K)
+        for e, st in zip(ev_end[p_], streams):
+            e.record(st)
+    torch.cuda.synchronize()
+    region_s = time.perf_counter() - t0
+    stages = smfg.profile_end()
+    ends = [max(ev_start.elapsed_time(e) for e in evs) * 1e-3 for evs in ev_end]
+    pass_s = sorted(b_ - a_ for a_, b_ in zip([0.0] + ends[:-1], ends))
+    dt = pass_s[len(pass_s) // 2] if len(pass_s) % 2 else 0.5 * (pass_s[len(pass_s) // 2 - 1] + pass_s[len(pass_s) // 2])
     gather_ms, gather_launches = stages["gather"]
-    gather_bytes = 2 * row_bytes * n_final
+    gather_bytes = 2 * row_bytes * n_final * passes
     gather_gbs = gather_bytes / (gather_ms * 1e-3) / 1e9 if gather_ms > 0 else 0.0
+    cnt_of_slot = {}
+    for q, (c, k, slot) in last_call.items():
+        cnt_of_slot[q] = [cnt[(c + b) % K] for b in range(k)]
 
     # The same gather launches once more with nothing else on the chip (the buffers of the last
     # launch sets are still in place): the kernel's own rate, next to the overlapped one above.
     smfg.profile_begin(1, 16)
     rows_alone = 0
-    timed_sets = [q for q, (c, k) in last_call.items() if c >= W]
+    full_sets = [q for q, (c, k, slot) in last_call.items() if k == max(v[1] for v in last_call.values())]
     for rep in range(6):
-        q = timed_sets[rep % len(timed_sets)]
-        c0, k = last_call[q][0] - W, last_call[q][1]
+        q = full_sets[rep % len(full_sets)]
+        k = last_call[q][1]
         smfg.gather_many(g, outs[q][:k], stream=streams[0])
-        rows_alone += sum(c[L] for c in cnt[c0:c0 + k])
+        rows_alone += sum(c[L] for c in cnt_of_slot[q])
     torch.cuda.synchronize()
     alone_ms, alone_launches = smfg.profile_end()["gather"]
     alone_gbs = 2 * row_bytes * rows_alone / (alone_ms * 1e-3) / 1e9 if alone_ms > 0 else 0.0
@@ -265,17 +390,17 @@ def main():
     # over the outermost block of the batches of the last launch set.
     consumer = None
     if feat.dtype in (torch.float16, torch.float32):
-        q = max(timed_sets, key=lambda t: last_call[t][1])
-        c0, k_set = last_call[q][0] - W, last_call[q][1]
+        q = full_sets[0]
+        k_set, slot_q = last_call[q][1], last_call[q][2]
+        cnt_q = cnt_of_slot[q]
         agg_out = torch.empty((outs[q][0].node_capacity, w.feat_dim), dtype=torch.float32, device=dev)
         smfg.profile_begin(2, 4 * G)
         agg_bytes = 0
         for rep in range(2):
             for b in range(k_set):
-                o, c = outs[q][b], cnt[c0 + b]
-                o.c.counts = counts_all.data_ptr() + (W + c0 + b) * stride
+                o, c = outs[q][b], cnt_q[b]
                 n_dst, e_last = c[L - 1], c[2 * L]
-                cview = counts_all[W + c0 + b]
+                cview = counts_ring[slot_q * G + b]
                 smfg.mean_aggregate(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.indptr[L - 1].numel() - 1, o.features,
                                     agg_out, stream=streams[0])
                 agg_bytes += e_last * row_bytes + 4 * e_last + 4 * (n_dst + 1) + 4 * w.feat_dim * n_dst
@@ -297,9 +422,9 @@ def main():
             lay_bytes = lay_flops = 0
             for rep in range(2):
                 for b in range(k_set):
-                    o, c = outs[q][b], cnt[c0 + b]
+                    o, c = outs[q][b], cnt_q[b]
                     n_dst, e_last = c[L - 1], c[2 * L]
-                    cview = counts_all[W + c0 + b]
+                    cview = counts_ring[slot_q * G + b]
                     smfg.sage_layer(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.indptr[L - 1].numel() - 1,
                                     o.features, lw, lb, True, lay_out, stream=streams[0])
                     lay_bytes += (e_last + n_dst) * row_bytes + 4 * e_last + 4 * (n_dst + 1) + 2 * hid * n_dst
@@ -313,11 +438,19 @@ def main():
                                  "TFLOPs": lay_flops / (lay_ms * 1e-3) / 1e12 if lay_ms > 0 else 0.0}
             del lay_out, lw, lb
 
+    traffic_row, traffic_note = (None, "not stored for an overridden feature width or row stride") \
+        if (args.feat_dim or args.row_stride) else stored_traffic(w.name, G)
     result = {
         "metric": "sampled mini-batches/sec (MFG build + feature gather)",
         "value": K / dt, "unit": "batches/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": dt / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
+        "timing": {"what": "median over `passes` passes of `steps` batches each, issued back to back and bracketed by "
+                           "device synchronisations; a pass ends when every stream has finished its work of the pass "
+                           "(HIP events on the issuing streams)",
+                   "passes": passes, "pass_ms_median": dt * 1e3, "pass_ms_min": pass_s[0] * 1e3,
+                   "pass_ms_max": pass_s[-1] * 1e3, "warmup_batches_run": warm + K,
+                   "region_s_host_clock": region_s, "region_batches_per_s": passes * K / region_s},
         "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {graph.num_edges} directed edges, "
                                f"features {w.feat_dim}x{str(w.feat_dtype).split('.')[-1]}, fanouts {list(w.fanouts)}, "
                                f"batch {w.batch_size}", "batches_per_call": G, "streams": S, "pipeline": bool(args.pipeline),
@@ -329,11 +462,13 @@ def main():
         "path_frac_of_hbm_peak": alg / dt / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": gather_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": gather_gbs / HBM_PEAK_GBS,
-                     "traffic": None if (args.feat_dim or args.row_stride) else MEASURED_GATHER_TRAFFIC_BYTES.get((w.name, G)), "traffic_unit": "bytes per launch",
-                     "avg_launch_ms": gather_ms / max(1, gather_launches),
-                     "note": "achieved is measured inside the timed region, where (with --pipeline 1) the gather "
-                             "shares the chip with the sampling kernels of the next launch set; alone_* is the same "
-                             "launch repeated right after with nothing else running",
+                     "traffic": traffic_row * n_final * passes / max(1, gather_launches) if traffic_row else None,
+                     "traffic_unit": "bytes per launch", "traffic_note": traffic_note,
+                     "avg_launch_ms": gather_ms / max(1, gather_launches), "launches": gather_launches,
+                     "note": "achieved = algorithmic bytes of all gather launches of the timed region / their summed "
+                             "durations (HIP events on the launch's own stream).  With --pipeline 1 every one of them "
+                             "but the very last shares the chip with the sampling kernels of the next launch set; "
+                             "alone_* is the same launch repeated right after with nothing else running",
                      "alone_achieved": alone_gbs, "alone_frac": alone_gbs / HBM_PEAK_GBS,
                      "alone_avg_launch_ms": alone_ms / max(1, alone_launches),
                      "algorithmic_bytes_per_launch": gather_bytes / max(1, gather_launches),
@@ -409,7 +544,7 @@ def main():
 
     if args.stages:
         smfg.profile_begin(2, 64 * (K // G + 2))
-        run_calls(W, K)
+        run_calls(0, K)
         st = smfg.profile_end()
         result["stage_ms_per_batch"] = {s: ms / K for s, (ms, _) in st.items()}
 
@@ -432,7 +567,7 @@ def main():
 
         def gpu_check(ref, i):
             o = outs[0][0]
-            o.c.counts = counts_all.data_ptr()
+            o.c.counts = counts_ring.data_ptr()
             smfg.sample_mfg(g, wss[0][0], batches[i], w.fanouts, keys[i], o)
             c = smfg.read_counts(o)
             n, e = c[:L + 1], c[L + 1:2 * L + 1]
@@ -444,7 +579,9 @@ def main():
             got = o.features[:n[L]].cpu().numpy().view(np.uint8).reshape(n[L], row_bytes)
             return bool(ok and np.array_equal(got, ref.features))
 
-        threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
+        share = os.environ.get("OMP_NUM_THREADS", "")
+        threads = args.cpu_threads or (int(share) if share.isdigit() and int(share) > 0
+                                       else len(os.sched_getaffinity(0)))
         result["cpu_baseline"] = cpu_baseline(w, graph, feat, batches, keys, args.cpu_seconds, threads, gpu_check)
 
     print(json.dumps(result), flush=True)
