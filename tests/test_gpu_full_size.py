@@ -12,11 +12,11 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _check_batches(w, graph, feat, g, orc, batches, batch_ids, per_call):
+def _check_batches(w, graph, feat, g, orc, batches, batch_ids, per_call, sample_capacity=0):
     """Runs the chosen batches `per_call` at a time and compares every output array.  The feature
     rows are checked against torch indexing of the same table with the oracle's node list."""
     L = len(w.fanouts)
-    wss = [smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(per_call)]
+    wss = [smfg.workspace_create(g, w.batch_size, w.fanouts, 0, sample_capacity) for _ in range(per_call)]
     outs = [smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(per_call)]
     for c0 in range(0, len(batch_ids), per_call):
         ids = batch_ids[c0:c0 + per_call]
@@ -38,16 +38,63 @@ def _check_batches(w, graph, feat, g, orc, batches, batch_ids, per_call):
             print(f"{w.name} batch {b}: nodes {n} edges {e} ok", flush=True)
 
 
-def test_large_workload_first_pass_batches():
-    """products-shaped workload (fp16 x 100: 200-byte rows), 8 batches per launch set."""
+@pytest.fixture(scope="module")
+def large():
     w = synth.WORKLOADS["large"]
     graph = synth.make_graph(w, device=DEV)
     feat = synth.make_features(w, device=DEV)
-    batches = synth.make_seed_batches(w, device=DEV)
     g = smfg.graph_create(graph.indptr, graph.indices, feat)
     orc = oracle.Oracle(graph.indptr.cpu().numpy(), graph.indices.cpu().numpy())
+    return graph, feat, g, orc
+
+
+def test_large_workload_first_pass_batches(large):
+    """products-shaped workload (fp16 x 100: 200-byte rows), 8 batches per launch set."""
+    graph, feat, g, orc = large
+    w = synth.WORKLOADS["large"]
+    batches = synth.make_seed_batches(w, device=DEV)
     ids = list(range(8)) + [len(batches) // 2, len(batches) - 1]
     _check_batches(w, graph, feat, g, orc, batches, ids, 8)
+
+
+@pytest.mark.parametrize("name", ["large_wide", "large_all"])
+def test_large_fanouts_and_full_neighbourhoods_at_full_size(large, name):
+    """The inference fanouts of section 5 / Table 6 on the products-shaped graph, in the launch
+    configuration the benchmark times (2 batches per launch set): fanouts (100,100) with 1024 seeds
+    (about 2.4 M sampled edges per batch) and full neighbourhoods (-1,-1) with 256 seeds (about
+    5.5 M edges per batch, more than the 4096 x 1024 samples one grid pass of the flat kernels
+    covers).  First four batches and the last one."""
+    graph, feat, g, orc = large
+    w = synth.WORKLOADS[name]
+    batches = synth.make_seed_batches(w, device=DEV)
+    ids = [0, 1, 2, 3, len(batches) - 1]
+    _check_batches(w, graph, feat, g, orc, batches, ids, 2, sample_capacity=min(graph.num_edges, (1 << 30) - 1))
+
+
+def test_wide_path_beyond_one_grid_pass(large):
+    """Full neighbourhoods for two hops, then a fanout of 2 over everything found: the last hop has
+    more than 4096 x 256 destinations and the second more than 4096 x 1024 samples, so the
+    destination-tile and sample-tile kernels of the exact-offset path each wrap around their grid."""
+    graph, feat, g, orc = large
+    w = synth.WORKLOADS["large_all"]
+    seeds = synth.make_seed_batches(w, device=DEV)[0]
+    fan = (-1, -1, 2)
+    key = 4242
+    ref = orc.sample_mfg(seeds.cpu().numpy(), fan, key, with_features=False)
+    assert ref.status == 0
+    assert ref.num_nodes[2] > 4096 * 256 and ref.num_edges[1] > 4096 * 1024
+    m = min(graph.num_edges, (1 << 30) - 1)
+    ws = smfg.workspace_create(g, seeds.numel(), fan, 0, m)
+    out = smfg.alloc_output(g, seeds.numel(), fan, with_features=False)
+    smfg.sample_mfg(g, ws, seeds, fan, key, out)
+    c = smfg.read_counts(out)
+    assert c == [int(x) for x in ref.counts]
+    n, e = c[:4], c[4:7]
+    assert np.array_equal(out.node_ids[:n[3]].cpu().numpy(), ref.node_ids)
+    for h in range(3):
+        assert np.array_equal(out.indptr[h][:n[h] + 1].cpu().numpy(), ref.indptr[h]), h
+        assert np.array_equal(out.indices[h][:e[h]].cpu().numpy(), ref.indices[h]), h
+    print(f"wide path beyond one grid pass: nodes {n} edges {e} ok", flush=True)
 
 
 @pytest.fixture(scope="module")
@@ -139,12 +186,9 @@ def test_mid_workload_full_pass():
     _full_pass(w, graph, feat, g, oracle.Oracle(graph.indptr.cpu().numpy(), graph.indices.cpu().numpy()))
 
 
-def test_large_workload_full_pass():
-    w = synth.WORKLOADS["large"]
-    graph = synth.make_graph(w, device=DEV)
-    feat = synth.make_features(w, device=DEV)
-    g = smfg.graph_create(graph.indptr, graph.indices, feat)
-    _full_pass(w, graph, feat, g, oracle.Oracle(graph.indptr.cpu().numpy(), graph.indices.cpu().numpy()))
+def test_large_workload_full_pass(large):
+    graph, feat, g, orc = large
+    _full_pass(synth.WORKLOADS["large"], graph, feat, g, orc)
 
 
 def test_papers_workload_full_pass(papers):
