@@ -49,6 +49,8 @@ struct BatchCtx {
   uint64_t* rec;         // (node << 32 | value) per known node and per sample, bucket by bucket
   uint32_t* hist;        // [blocks x buckets] records per (row block, bucket), later their offsets
   uint32_t* bstart;      // [buckets + 1] first record of each bucket; [buckets + 1 .. 2 buckets + 1) bucket sizes
+  uint64_t* rec2;        // the records once more, each bucket split into sub-buckets (hops with lg2 > 0)
+  uint32_t* bstart2;     // [buckets * sub-buckets + 1] first record of each sub-bucket in rec2
 };
 
 struct Launch {
@@ -65,6 +67,7 @@ struct Launch {
   int32_t d;       // its fanout
   int32_t G;       // batches
   int32_t lgB;     // partition path: log2 of the hash buckets of this hop
+  int32_t lg2;     // partition path: log2 of the sub-buckets each bucket is split into (0: not split)
   int32_t block_rows;  // partition path: destinations per row block of this hop
   BatchCtx b[SMFG_MAX_BATCHES];
 };

@@ -1,5 +1,4 @@
-// libsmfg partition strategy for the dedup of a hop (fanouts up to SMFG_MAX_FANOUT, hops whose
-// nodes + samples fit kPartMaxRecords).
+// libsmfg partition strategy for the dedup of a hop (fanouts up to SMFG_MAX_FANOUT).
 //
 // Procedure OneHopMFG keeps one map from global to local ids and gives a node its local id at the
 // first encounter.  Here the map never exists as one structure in memory.  Per hop:
@@ -9,6 +8,9 @@
 //                 (value = tag | scan position);
 //   scan_hist     turns the counts of a bucket over the row blocks into offsets, bucket sizes;
 //   scatter       moves the records into their buckets (one contiguous range of `rec` each);
+//   split_buckets only for hops with more records than 1024 buckets of the target size hold: one
+//                 block per bucket orders the bucket's records by further hash bits into
+//                 sub-buckets (`rec2`), which then take the place of the buckets;
 //   dedup_buckets one block per bucket builds a hash table of the bucket's nodes in LDS, keeping
 //                 the smallest value per node (a known node's local id always wins, else the
 //                 earliest scan position).  A sample that is its node's first appearance keeps
@@ -28,12 +30,12 @@
 
 namespace smfg_dev {
 
-constexpr int kPartMaxLgB = 10;                     // at most 1024 buckets per hop
+constexpr int kPartMaxLgB = 10;                     // at most 1024 buckets per hop ...
+constexpr int kPartMaxLg2 = 10;                     // ... each split into at most 1024 sub-buckets
 constexpr int kPartTableLg = 12;                    // LDS table: 4096 slots of 8 bytes
 constexpr uint32_t kPartSlots = 1u << kPartTableLg;
 constexpr int kPartBucketRecords = 2048;            // buckets are sized for at most this many on average
-constexpr int64_t kPartMaxRecords = static_cast<int64_t>(kPartBucketRecords) << kPartMaxLgB;
-constexpr int kPartMaxRowBlocks = 512;              // row blocks per batch and hop (plus a ragged one)
+constexpr int64_t kPartMaxRecords = static_cast<int64_t>(kPartBucketRecords) << (kPartMaxLgB + kPartMaxLg2);
 constexpr uint32_t kPartHash = 0x9E3779B1u;         // odd: node -> node * kPartHash is a bijection on 32 bits
 constexpr uint32_t kResolved = 0x80000000u;         // gsrc entry: low 30 bits = final local id of a known node
 constexpr uint32_t kPointer = 0xC0000000u;          // gsrc entry: low 30 bits = position of the first appearance
@@ -284,6 +286,119 @@ __global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
   }
 }
 
+// One block per bucket: the bucket's records, ordered by the lg2 hash bits below the bucket's,
+// go to the same range of rec2; the sub-buckets' first records go to bstart2.  Counting pass, then
+// rounds of kScatterRound records staged in LDS like in k_scatter.
+__global__ void __launch_bounds__(kThreads) k_split_buckets(const Launch P) {
+  __shared__ uint32_t gbase[1 << kPartMaxLg2];
+  __shared__ uint32_t cnt[1 << kPartMaxLg2];
+  __shared__ uint32_t lstart[1 << kPartMaxLg2];
+  __shared__ unsigned long long stage[kScatterRound];
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const uint32_t b1 = static_cast<uint32_t>(block_in_batch(P));
+  const uint32_t nB1 = 1u << P.lgB;
+  if (b1 >= nB1) return;
+  const int n2 = 1 << P.lg2;
+  const int shift = 32 - P.lgB - P.lg2;
+  const uint32_t mask = static_cast<uint32_t>(n2 - 1);
+  const uint32_t rec0 = B.bstart[b1];
+  const uint32_t rec1 = rec0 + B.bstart[nB1 + 1 + b1];
+  constexpr int per = (1 << kPartMaxLg2) / kThreads;
+  for (int b = threadIdx.x; b < n2; b += kThreads) cnt[b] = 0u;
+  __syncthreads();
+  for (uint32_t c0 = rec0; c0 < rec1; c0 += kScatterRound) {
+    unsigned long long r[kScatterPer];
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u) {
+      const uint32_t q = c0 + u * kThreads + threadIdx.x;
+      r[u] = q < rec1 ? B.rec[q] : kEmpty;
+    }
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u)
+      if (r[u] != kEmpty) atomicAdd(&cnt[((static_cast<uint32_t>(r[u] >> 32) * kPartHash) >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  {
+    uint32_t c[per];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      c[u] = b < n2 ? cnt[b] : 0u;
+      mine += c[u];
+    }
+    unsigned long long total;
+    uint32_t pre = rec0 + static_cast<uint32_t>(block_exscan(mine, lds, total));
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      if (b < n2) {
+        gbase[b] = pre;
+        B.bstart2[(static_cast<size_t>(b1) << P.lg2) + b] = pre;
+      }
+      pre += c[u];
+    }
+    if (b1 == nB1 - 1 && threadIdx.x == 0) B.bstart2[static_cast<size_t>(nB1) << P.lg2] = rec1;
+  }
+  for (uint32_t c0 = rec0; c0 < rec1; c0 += kScatterRound) {
+    __syncthreads();
+    for (int b = threadIdx.x; b < n2; b += kThreads) cnt[b] = 0u;
+    __syncthreads();
+    unsigned long long r[kScatterPer];
+    uint32_t bk[kScatterPer], rk[kScatterPer];
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u) {
+      const uint32_t q = c0 + u * kThreads + threadIdx.x;
+      r[u] = q < rec1 ? B.rec[q] : kEmpty;
+    }
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u) {
+      bk[u] = 0u;
+      rk[u] = 0u;
+      if (r[u] != kEmpty) {
+        bk[u] = ((static_cast<uint32_t>(r[u] >> 32) * kPartHash) >> shift) & mask;
+        rk[u] = atomicAdd(&cnt[bk[u]], 1u);
+      }
+    }
+    __syncthreads();
+    uint32_t c[per];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      c[u] = b < n2 ? cnt[b] : 0u;
+      mine += c[u];
+    }
+    unsigned long long total;
+    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      if (b < n2) lstart[b] = pre;
+      pre += c[u];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u)
+      if (r[u] != kEmpty) stage[lstart[bk[u]] + rk[u]] = r[u];
+    __syncthreads();
+    const uint32_t staged = static_cast<uint32_t>(total);
+    for (uint32_t t = threadIdx.x; t < staged; t += kThreads) {
+      const unsigned long long x = stage[t];
+      const uint32_t b = ((static_cast<uint32_t>(x >> 32) * kPartHash) >> shift) & mask;
+      B.rec2[gbase[b] + (t - lstart[b])] = x;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      if (b < n2) gbase[b] += c[u];
+    }
+  }
+}
+
 // One block per bucket.  All records of a node are in one bucket, so the bucket's table in LDS
 // sees every occurrence of its nodes.  A bucket with more records than the table takes is
 // handled in 2^lgR rounds, round r taking the nodes whose next lgR hash bits equal r; should a
@@ -297,12 +412,14 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
   if (block_has_status(B, P.L)) return;
   const uint32_t bucket = static_cast<uint32_t>(block_in_batch(P));
   const uint32_t nB = 1u << P.lgB;
-  if (bucket >= nB) return;
-  const uint32_t rec0 = B.bstart[bucket];
-  const uint32_t rec1 = rec0 + B.bstart[nB + 1 + bucket];
+  if (bucket >= (nB << P.lg2)) return;
+  // the (sub-)bucket's records
+  const uint64_t* __restrict__ recs = P.lg2 == 0 ? B.rec : B.rec2;
+  const uint32_t rec0 = P.lg2 == 0 ? B.bstart[bucket] : B.bstart2[bucket];
+  const uint32_t rec1 = P.lg2 == 0 ? rec0 + B.bstart[nB + 1 + bucket] : B.bstart2[bucket + 1];
   const uint32_t cnt = rec1 - rec0;
   if (cnt == 0) return;
-  const int free_bits = 32 - P.lgB;  // hash bits below the bucket's
+  const int free_bits = 32 - P.lgB - P.lg2;  // hash bits below the (sub-)bucket's
   const int max_lgR = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
   int lgR = 0;
   while (lgR < max_lgR && (cnt >> lgR) > kPartSlots / 2) ++lgR;
@@ -320,7 +437,7 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const uint32_t r = c0 + u * kThreads + threadIdx.x;
-          mine[u] = r < rec1 ? B.rec[r] : kEmpty;
+          mine[u] = r < rec1 ? recs[r] : kEmpty;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -351,7 +468,7 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             const uint32_t r = c0 + u * kThreads + threadIdx.x;
-            mine[u] = r < rec1 ? B.rec[r] : kEmpty;
+            mine[u] = r < rec1 ? recs[r] : kEmpty;
           }
 #pragma unroll
           for (int u = 0; u < U; ++u) {

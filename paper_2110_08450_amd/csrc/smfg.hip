@@ -147,7 +147,8 @@ struct smfg_workspace {
   bool part;
   int64_t rec_entries;   // capacity of rec: known nodes + samples of a hop
   int64_t hist_entries;  // capacity of hist: row blocks x buckets of a hop
-  int64_t b_table, b_slot, b_row, b_tiles, b_stiles, b_rec, b_hist, b_bstart;  // byte sizes of the slab's parts
+  int split_lg;          // log2 of the most sub-buckets a hop needs (0: no hop splits its buckets)
+  int64_t b_table, b_slot, b_row, b_tiles, b_stiles, b_rec, b_hist, b_bstart, b_bstart2;  // byte sizes of the slab's parts
   uint32_t table_log2;
   void* slab;
   uint64_t* table;
@@ -165,6 +166,8 @@ struct smfg_workspace {
   uint64_t* rec;
   uint32_t* hist;
   uint32_t* bstart;
+  uint64_t* rec2;
+  uint32_t* bstart2;
 };
 
 namespace {
@@ -201,11 +204,13 @@ int check_fanouts(int32_t L, const int32_t* fanouts, bool* wide = nullptr) {
 
 inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 
-// Launch shape of one hop under the partition strategy: 2^lgB hash buckets sized for at most
-// kPartBucketRecords records on average in the worst case, destinations cut into at most
-// kPartMaxRowBlocks (+1) row blocks that are whole multiples of what a thread block draws at once.
+// Launch shape of one hop under the partition strategy: 2^lgB hash buckets (at most 1024), each
+// split once more into 2^lg2 sub-buckets if the records would otherwise exceed kPartBucketRecords
+// per bucket on average in the worst case; destinations cut into row blocks that are whole
+// multiples of what a thread block draws at once, at most 512 of them (more for hops beyond
+// 256 K destinations, up to 4096).
 struct HopPlan {
-  int lgB;
+  int lgB, lg2;
   int block_rows;
   int64_t row_blocks;
 };
@@ -213,10 +218,14 @@ struct HopPlan {
 HopPlan plan_hop(int64_t max_rows, int d) {
   HopPlan hp;
   const int64_t records = max_rows * (1 + d);
-  hp.lgB = 0;
-  while (hp.lgB < kPartMaxLgB && (records >> hp.lgB) > kPartBucketRecords) ++hp.lgB;
+  int lg = 0;
+  while (lg < kPartMaxLgB + kPartMaxLg2 && (records >> lg) > kPartBucketRecords) ++lg;
+  hp.lgB = lg < kPartMaxLgB ? lg : kPartMaxLgB;
+  hp.lg2 = lg - hp.lgB;
+  int64_t cap = (max_rows + 511) / 512;
+  cap = cap < 512 ? 512 : (cap > 4096 ? 4096 : cap);
   hp.block_rows = (64 / d) * (kThreads / 64);
-  while ((max_rows + hp.block_rows - 1) / hp.block_rows > kPartMaxRowBlocks) hp.block_rows *= 2;
+  while ((max_rows + hp.block_rows - 1) / hp.block_rows > cap) hp.block_rows *= 2;
   hp.row_blocks = (max_rows + hp.block_rows - 1) / hp.block_rows;
   if (hp.row_blocks < 1) hp.row_blocks = 1;
   return hp;
@@ -239,10 +248,11 @@ bool hop_row_bounds(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_
 
 // Whether every hop of a call can take the partition strategy; if so, what it needs of a workspace.
 bool part_needs(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t num_nodes, int64_t node_capacity,
-                int64_t* rec_entries, int64_t* hist_entries) {
+                int64_t* rec_entries, int64_t* hist_entries, int* split_lg) {
   int64_t rows[SMFG_MAX_LAYERS];
   *rec_entries = 1;
   *hist_entries = 1;
+  *split_lg = 0;
   for (int h = 0; h < L; ++h)
     if (fanouts[h] < 1 || fanouts[h] > SMFG_MAX_FANOUT) return false;
   if (!hop_row_bounds(num_seeds, L, fanouts, num_nodes, node_capacity, rows)) return false;
@@ -252,6 +262,7 @@ bool part_needs(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t nu
     const HopPlan hp = plan_hop(rows[h], fanouts[h]);
     if (records > *rec_entries) *rec_entries = records;
     if ((hp.row_blocks << hp.lgB) > *hist_entries) *hist_entries = hp.row_blocks << hp.lgB;
+    if (hp.lg2 > 0 && hp.lgB + hp.lg2 > *split_lg) *split_lg = hp.lgB + hp.lg2;
   }
   return true;
 }
@@ -290,7 +301,8 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
   ws->slot_entries = slots > 0 ? slots : 1;
   ws->table_log2 = lg;
   ws->part = !table_forced() &&
-             part_needs(max_seeds, L, fanouts, g->num_nodes, node_capacity, &ws->rec_entries, &ws->hist_entries) &&
+             part_needs(max_seeds, L, fanouts, g->num_nodes, node_capacity, &ws->rec_entries, &ws->hist_entries,
+                        &ws->split_lg) &&
              slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity) <= ws->slot_entries;
   const int64_t tiles = (node_capacity + kTileRows - 1) / kTileRows + 1;
   ws->b_slot = align256(ws->slot_entries * 4);
@@ -300,7 +312,9 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
     ws->b_rec = align256(ws->rec_entries * 8);
     ws->b_hist = align256(ws->hist_entries * 4);
     ws->b_bstart = align256((2 * (int64_t(1) << kPartMaxLgB) + 2) * 4);
-    ws->bytes = ws->b_slot + 4 * ws->b_row + ws->b_tiles + ws->b_rec + ws->b_hist + ws->b_bstart;
+    ws->b_bstart2 = ws->split_lg > 0 ? align256(((int64_t(1) << ws->split_lg) + 2) * 4) : 0;
+    ws->bytes = ws->b_slot + 4 * ws->b_row + ws->b_tiles + (ws->split_lg > 0 ? 2 : 1) * ws->b_rec + ws->b_hist +
+                ws->b_bstart + ws->b_bstart2;
   } else {
     ws->b_table = align256((int64_t(1) << lg) * 8);
     ws->b_stiles = align256((ws->slot_entries / kWideTile + 2) * 8);
@@ -320,7 +334,11 @@ void bind_workspace(smfg_workspace* ws, void* base) {
   if (ws->part) {
     ws->rec = reinterpret_cast<uint64_t*>(p); p += ws->b_rec;
     ws->hist = reinterpret_cast<uint32_t*>(p); p += ws->b_hist;
-    ws->bstart = reinterpret_cast<uint32_t*>(p);
+    ws->bstart = reinterpret_cast<uint32_t*>(p); p += ws->b_bstart;
+    if (ws->split_lg > 0) {
+      ws->bstart2 = reinterpret_cast<uint32_t*>(p); p += ws->b_bstart2;
+      ws->rec2 = reinterpret_cast<uint64_t*>(p);
+    }
     return;
   }
   ws->table = reinterpret_cast<uint64_t*>(p); p += ws->b_table;
@@ -613,6 +631,8 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     B.rec = w->rec;
     B.hist = w->hist;
     B.bstart = w->bstart;
+    B.rec2 = w->rec2;
+    B.bstart2 = w->bstart2;
     B.features = static_cast<uint8_t*>(o.features);
     if (o.labels) {
       if (!g->labels) return SMFG_ERR_INVALID_ARG;
@@ -655,7 +675,8 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       plan[h] = plan_hop(max_n[h], fanouts[h]);
       const int64_t records = max_n[h] * (1 + fanouts[h]);
       for (int b = 0; b < num_batches; ++b)
-        if (records > ws[b]->rec_entries || (plan[h].row_blocks << plan[h].lgB) > ws[b]->hist_entries)
+        if (records > ws[b]->rec_entries || (plan[h].row_blocks << plan[h].lgB) > ws[b]->hist_entries ||
+            (plan[h].lg2 > 0 && plan[h].lgB + plan[h].lg2 > ws[b]->split_lg))
           return SMFG_ERR_CAPACITY;
     }
   }
@@ -688,6 +709,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     const unsigned tile_blocks = blocks_for(rows, kTileRows, kCap);
     if (part) {
       P.lgB = plan[h].lgB;
+      P.lg2 = plan[h].lg2;
       P.block_rows = plan[h].block_rows;
       const unsigned row_blocks = static_cast<unsigned>(plan[h].row_blocks);
       const unsigned buckets = 1u << P.lgB;
@@ -699,10 +721,11 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
         StageTimer t_(SMFG_STAGE_PARTITION, st);
         k_scan_hist<<<((buckets + kScanCols - 1) / kScanCols) * G, kThreads, 0, st>>>(P);
         k_scatter<<<row_blocks * G, kThreads, 0, st>>>(P);
+        if (P.lg2 > 0) k_split_buckets<<<buckets * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_DEDUP, st);
-        k_dedup_buckets<<<buckets * G, kThreads, 0, st>>>(P);
+        k_dedup_buckets<<<(buckets << P.lg2) * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_FLAG, st);

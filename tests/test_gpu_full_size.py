@@ -97,6 +97,31 @@ def test_wide_path_beyond_one_grid_pass(large):
     print(f"wide path beyond one grid pass: nodes {n} edges {e} ok", flush=True)
 
 
+def test_half_a_million_seeds_split_buckets(large):
+    """One batch of 500 000 seeds with fanouts (32, 2) on the products-shaped graph: 16 M and 7 M
+    records per hop, so the hash buckets of both hops are split into sub-buckets before the dedup
+    (the same path the inference-shaped workload takes on the larger graph)."""
+    graph, feat, g, orc = large
+    w = synth.WORKLOADS["large"]
+    seeds = synth.node_permutation(w.num_nodes, w.graph_seed, device=DEV)[:500_000].to(torch.int32).contiguous()
+    fan = (32, 2)
+    key = 99
+    ref = orc.sample_mfg(seeds.cpu().numpy(), fan, key, with_features=False)
+    assert ref.status == 0
+    ws = smfg.workspace_create(g, seeds.numel(), fan)
+    out = smfg.alloc_output(g, seeds.numel(), fan, with_features=False)
+    for rep in range(2):
+        smfg.sample_mfg(g, ws, seeds, fan, key, out)
+        c = smfg.read_counts(out)
+        assert c == [int(x) for x in ref.counts]
+        n, e = c[:3], c[3:5]
+        assert np.array_equal(out.node_ids[:n[2]].cpu().numpy(), ref.node_ids)
+        for h in range(2):
+            assert np.array_equal(out.indptr[h][:n[h] + 1].cpu().numpy(), ref.indptr[h]), h
+            assert np.array_equal(out.indices[h][:e[h]].cpu().numpy(), ref.indices[h]), h
+    print(f"500 000 seeds: nodes {n} edges {e} ok", flush=True)
+
+
 @pytest.fixture(scope="module")
 def papers():
     w = synth.WORKLOADS["papers"]
