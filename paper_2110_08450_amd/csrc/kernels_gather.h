@@ -30,6 +30,11 @@ __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, in
   }
   __syncthreads();
   V* __restrict__ o = reinterpret_cast<V*>(out) + static_cast<uint64_t>(r0) * vec_per_row;
+  // (row, column) of a vector of the chunk by multiplication: ceil(2^32 / vec_per_row) gives the
+  // exact quotient as long as index * vec_per_row < 2^32, which holds for every index of a chunk
+  // when a row has at most 8192 vectors; longer rows divide
+  const bool by_mul = vec_per_row <= 8192u;
+  const uint64_t inv = 0xFFFFFFFFull / vec_per_row + 1ull;
   uint32_t base = threadIdx.x;
   // full rounds: U independent row reads in flight per thread, then the U stores
   for (; base + (U - 1) * kThreads < cnt; base += kThreads * U) {
@@ -37,7 +42,7 @@ __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, in
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t idx = base + u * kThreads;
-      const uint32_t jrow = idx / vec_per_row;
+      const uint32_t jrow = by_mul ? static_cast<uint32_t>((idx * inv) >> 32) : idx / vec_per_row;
       const uint32_t c = idx - jrow * vec_per_row;
       val[u] = __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c);
     }
@@ -45,7 +50,7 @@ __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, in
     for (int u = 0; u < U; ++u) __builtin_nontemporal_store(val[u], o + base + u * kThreads);
   }
   for (; base < cnt; base += kThreads) {
-    const uint32_t jrow = base / vec_per_row;
+    const uint32_t jrow = by_mul ? static_cast<uint32_t>((base * inv) >> 32) : base / vec_per_row;
     const uint32_t c = base - jrow * vec_per_row;
     __builtin_nontemporal_store(
         __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c), o + base);

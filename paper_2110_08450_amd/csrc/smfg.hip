@@ -247,6 +247,23 @@ bool hop_row_bounds(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_
 }
 
 // Whether every hop of a call can take the partition strategy; if so, what it needs of a workspace.
+// The environment variable SMFG_DEDUP=table makes new workspaces use the table strategy even
+// where the partition strategy applies (for measuring one against the other).
+bool table_forced() {
+  const char* e = std::getenv("SMFG_DEDUP");
+  return e && std::strcmp(e, "table") == 0;
+}
+// ... and SMFG_DEDUP=partition the partition strategy also for calls so small that the table
+// strategy would be chosen (so that tests reach it with small inputs).
+bool part_forced() {
+  const char* e = std::getenv("SMFG_DEDUP");
+  return e && std::strcmp(e, "partition") == 0;
+}
+
+// Calls whose largest hop stays below kPartMinRecords keep the table strategy: its four launches per
+// hop cost less than the partition strategy's seven when every kernel is launch-bound anyway.
+constexpr int64_t kPartMinRecords = 32768;
+
 bool part_needs(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t num_nodes, int64_t node_capacity,
                 int64_t* rec_entries, int64_t* hist_entries, int* split_lg) {
   int64_t rows[SMFG_MAX_LAYERS];
@@ -264,14 +281,8 @@ bool part_needs(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t nu
     if ((hp.row_blocks << hp.lgB) > *hist_entries) *hist_entries = hp.row_blocks << hp.lgB;
     if (hp.lg2 > 0 && hp.lgB + hp.lg2 > *split_lg) *split_lg = hp.lgB + hp.lg2;
   }
+  if (*rec_entries < kPartMinRecords && !part_forced()) return false;
   return true;
-}
-
-// The environment variable SMFG_DEDUP=table makes new workspaces use the table strategy even
-// where the partition strategy applies (for measuring one against the other).
-bool table_forced() {
-  const char* e = std::getenv("SMFG_DEDUP");
-  return e && std::strcmp(e, "table") == 0;
 }
 
 // Sizes of a workspace for up to max_seeds seeds, the given fanouts and capacities: fills every

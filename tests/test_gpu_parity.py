@@ -14,13 +14,11 @@ DEV = "cuda:0"
 
 @pytest.fixture(autouse=True, params=["partition", "table"])
 def dedup_strategy(request, monkeypatch):
-    """Every test of this file runs with both dedup strategies of the fast path: the default (hash
-    partition, no global table) and the global table (what large hops and wide fanouts use), which
-    the environment variable SMFG_DEDUP=table selects for workspaces created while it is set."""
-    if request.param == "table":
-        monkeypatch.setenv("SMFG_DEDUP", "table")
-    else:
-        monkeypatch.delenv("SMFG_DEDUP", raising=False)
+    """Every test of this file runs with both dedup strategies of the fast path: the hash partition
+    (no global table; the default unless every hop of a call is small) and the global table (what
+    small calls and wide fanouts use).  The environment variable SMFG_DEDUP selects one for the
+    workspaces created while it is set."""
+    monkeypatch.setenv("SMFG_DEDUP", request.param)   # also for calls whose size alone would pick the other
     return request.param
 
 
@@ -143,6 +141,24 @@ def test_gather_row_widths(dim, dtype):
     torch.cuda.synchronize()
     assert torch.equal(out[:ids.numel()], gg.feat[ids.long()])
     assert (out[ids.numel():] == 0).all()
+
+
+def test_gather_very_long_rows():
+    """Rows of more than 8192 sixteen-byte vectors (and of an odd number of 4-byte ones): the row /
+    column split of the gather's flat index takes its division path."""
+    rng = np.random.default_rng(31)
+    adj = random_simple_graph(60, 6, rng)
+    indptr, indices = csr_from_adj(adj)
+    for dim in (4 * 8200, 8200 + 1):
+        feat = rng.integers(-2**31, 2**31 - 1, size=(60, dim), dtype=np.int64).astype(np.int32).view(np.float32)
+        gg = GpuGraph(indptr, indices, feat)
+        ids = torch.from_numpy(rng.permutation(60).astype(np.int32)).to(DEV)
+        n = torch.tensor([45], dtype=torch.int64, device=DEV)
+        out = torch.zeros((60, dim), dtype=torch.float32, device=DEV)
+        smfg.gather_rows(gg.g, ids, n, 60, out)
+        torch.cuda.synchronize()
+        assert torch.equal(out[:45].view(torch.int32), gg.feat[ids[:45].long()].view(torch.int32))
+        assert (out[45:].view(torch.int32) == 0).all()
 
 
 def test_ragged_batches_in_one_call(tiny):
