@@ -26,6 +26,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+# Launch configuration per workload: (batches per launch set, sampling streams, buffer sets).
+# Small batches are bound by the latency of the chain of short kernels, so they take more batches
+# per set and two sampling streams; the largest batches fill the chip one at a time.
+LAUNCH_CONFIG = {"tiny": (4, 1, 2), "mid": (16, 2, 3), "large": (8, 1, 2), "papers": (8, 1, 2),
+                 "papers_infer": (1, 2, 3), "large_wide": (2, 1, 2), "large_all": (2, 1, 2)}
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 
 
@@ -179,16 +185,17 @@ def main():
     ap.add_argument("--steps", type=int, default=4096)
     ap.add_argument("--warmup", type=int, default=64)
     ap.add_argument("--workload", default="papers")
-    ap.add_argument("--batches-per-call", type=int, default=8)
+    ap.add_argument("--batches-per-call", type=int, default=0,
+                    help="batches per launch set (0 = the workload's entry in LAUNCH_CONFIG, else 8)")
     ap.add_argument("--streams", type=int, default=1,
                     help="launch sets alternate over this many HIP streams, each with its own workspaces")
     ap.add_argument("--pipeline", type=int, default=1,
                     help="1: gather of launch set i runs on a second stream while set i+1 is sampled (two "
                          "buffer sets); 0: every launch set runs start to end on one stream (see --streams)")
     ap.add_argument("--feat-dim", type=int, default=0, help="experiment: override the feature width")
-    ap.add_argument("--depth", type=int, default=2, help="buffer sets of the pipelined run")
-    ap.add_argument("--sample-streams", type=int, default=1,
-                    help="pipelined run: launch sets alternate over this many sampling streams (needs depth > streams)")
+    ap.add_argument("--depth", type=int, default=0, help="buffer sets of the pipelined run (0 = LAUNCH_CONFIG, else 2)")
+    ap.add_argument("--sample-streams", type=int, default=0,
+                    help="pipelined run: launch sets alternate over this many sampling streams (needs depth > streams; 0 = LAUNCH_CONFIG, else 1)")
     ap.add_argument("--row-stride", type=int, default=0,
                     help="experiment: feature row stride in bytes (>= row bytes; 0 = dense rows)")
     ap.add_argument("--passes", type=int, default=0,
@@ -243,6 +250,10 @@ def main():
     log(f"[gen] features {tuple(feat.shape)} {feat.dtype}, {len(batches)} seed batches, {time.time() - t0:.1f}s")
     torch.cuda.empty_cache()
 
+    cfg = LAUNCH_CONFIG.get(w.name, (8, 1, 2))
+    args.batches_per_call = args.batches_per_call or cfg[0]
+    args.sample_streams = args.sample_streams or cfg[1]
+    args.depth = args.depth or max(cfg[2], args.sample_streams + 1)
     G = max(1, min(args.batches_per_call, smfg.MAX_BATCHES))
     L = len(w.fanouts)
     g = smfg.graph_create(graph.indptr, graph.indices, feat)
@@ -253,7 +264,8 @@ def main():
         from paper_2110_08450_amd.pipeline import BatchPipeline
         pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G, sample_capacity=scap,
                              depth=max(2, args.depth, args.sample_streams + 1), sample_streams=args.sample_streams)
-        S, streams, wss, outs = 2, [pipe.s_sample, pipe.s_gather], pipe.wss, pipe.outs
+        streams, wss, outs = pipe.s_samples + [pipe.s_gather], pipe.wss, pipe.outs
+        S = len(streams)
     else:
         S = max(1, args.streams)
         streams = [torch.cuda.Stream() for _ in range(S)]
@@ -454,6 +466,8 @@ def main():
         "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {graph.num_edges} directed edges, "
                                f"features {w.feat_dim}x{str(w.feat_dtype).split('.')[-1]}, fanouts {list(w.fanouts)}, "
                                f"batch {w.batch_size}", "batches_per_call": G, "streams": S, "pipeline": bool(args.pipeline),
+                   "sample_streams": args.sample_streams if args.pipeline else None,
+                   "buffer_sets": depth,
                    "row_stride_bytes": int(feat.stride(0) * feat.element_size()),
                    "mean_nodes_per_batch": n_final / K, "mean_edges_per_batch": edges / K},
         "sampled_edges_per_s": edges / dt,

@@ -69,6 +69,8 @@ struct Launch {
   int32_t lgB;     // partition path: log2 of the hash buckets of this hop
   int32_t lg2;     // partition path: log2 of the sub-buckets each bucket is split into (0: not split)
   int32_t block_rows;  // partition path: destinations per row block of this hop
+  int32_t flat;    // partition path over exact offsets: lgB / lg2 are upper bounds, the hop's own
+                   // shape follows from its record count on the device (hop_shape)
   BatchCtx b[SMFG_MAX_BATCHES];
 };
 static_assert(sizeof(Launch) <= 4096, "kernel arguments are limited to 4 KB");

@@ -44,6 +44,32 @@ __device__ __forceinline__ uint32_t part_bucket(uint32_t node, int lgB) {
   return lgB == 0 ? 0u : (node * kPartHash) >> (32 - lgB);
 }
 
+// Buckets (2^lgB) and sub-buckets per bucket (2^lg2) of the current hop.  Padded positions: as the
+// host planned them from the worst case.  Exact offsets (P.flat): the worst case of a hop that
+// takes whole neighbourhoods is far above what a batch draws, so the shape follows the hop's
+// actual record count (known nodes + samples, both final before the first kernel that asks) and
+// the host's figures only bound it; grids are sized for the bound and surplus blocks leave.
+constexpr int kFlatBlock = 8192;  // stream elements (known nodes, then samples) per block of the flat kernels
+struct HopShape {
+  int lgB, lg2;
+};
+__device__ __forceinline__ HopShape hop_shape(const Launch& P, const BatchCtx& B) {
+  HopShape s{P.lgB, P.lg2};
+  if (P.flat) {
+    const long long records = B.counts[P.h] + B.counts[P.L + 1 + P.h];
+    int lg = 0;
+    while (lg < P.lgB + P.lg2 && (records >> lg) > kPartBucketRecords) ++lg;
+    s.lgB = lg < P.lgB ? lg : P.lgB;
+    s.lg2 = lg - s.lgB;
+  }
+  return s;
+}
+// Row blocks (padded positions) or flat blocks (exact offsets) of the current hop.
+__device__ __forceinline__ int hop_blocks(const Launch& P, const BatchCtx& B) {
+  if (P.flat) return static_cast<int>((B.counts[P.h] + B.counts[P.L + 1 + P.h] + kFlatBlock - 1) / kFlatBlock);
+  return static_cast<int>((B.counts[P.h] + P.block_rows - 1) / P.block_rows);
+}
+
 // counts <- (n_0, 0, ..., status 0); node_ids[0, n_0) <- seeds; labels of the seeds.  Seeds are
 // range-checked by the first hop's k_sample_hist, which runs after the status word is zero.
 __global__ void __launch_bounds__(kThreads) k_begin(const Launch P) {
@@ -108,9 +134,8 @@ __global__ void __launch_bounds__(kThreads) k_scan_hist(const Launch P) {
   __shared__ uint32_t part[kScanSegs][kScanCols];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
-  const int n = static_cast<int>(B.counts[P.h]);
-  const int blocks = (n + P.block_rows - 1) / P.block_rows;
-  const int nB = 1 << P.lgB;
+  const int blocks = hop_blocks(P, B);
+  const int nB = 1 << hop_shape(P, B).lgB;
   const int c = threadIdx.x % kScanCols, seg = threadIdx.x / kScanCols;
   const int b = block_in_batch(P) * kScanCols + c;
   const int per = (blocks + kScanSegs - 1) / kScanSegs;
@@ -297,11 +322,12 @@ __global__ void __launch_bounds__(kThreads) k_split_buckets(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
+  const HopShape hs = hop_shape(P, B);
   const uint32_t b1 = static_cast<uint32_t>(block_in_batch(P));
-  const uint32_t nB1 = 1u << P.lgB;
-  if (b1 >= nB1) return;
-  const int n2 = 1 << P.lg2;
-  const int shift = 32 - P.lgB - P.lg2;
+  const uint32_t nB1 = 1u << hs.lgB;
+  if (hs.lg2 == 0 || b1 >= nB1) return;
+  const int n2 = 1 << hs.lg2;
+  const int shift = 32 - hs.lgB - hs.lg2;
   const uint32_t mask = static_cast<uint32_t>(n2 - 1);
   const uint32_t rec0 = B.bstart[b1];
   const uint32_t rec1 = rec0 + B.bstart[nB1 + 1 + b1];
@@ -336,11 +362,11 @@ __global__ void __launch_bounds__(kThreads) k_split_buckets(const Launch P) {
       const int b = threadIdx.x * per + u;
       if (b < n2) {
         gbase[b] = pre;
-        B.bstart2[(static_cast<size_t>(b1) << P.lg2) + b] = pre;
+        B.bstart2[(static_cast<size_t>(b1) << hs.lg2) + b] = pre;
       }
       pre += c[u];
     }
-    if (b1 == nB1 - 1 && threadIdx.x == 0) B.bstart2[static_cast<size_t>(nB1) << P.lg2] = rec1;
+    if (b1 == nB1 - 1 && threadIdx.x == 0) B.bstart2[static_cast<size_t>(nB1) << hs.lg2] = rec1;
   }
   for (uint32_t c0 = rec0; c0 < rec1; c0 += kScatterRound) {
     __syncthreads();
@@ -410,16 +436,17 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
   __shared__ int overflow_lds;
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
+  const HopShape hs = hop_shape(P, B);
   const uint32_t bucket = static_cast<uint32_t>(block_in_batch(P));
-  const uint32_t nB = 1u << P.lgB;
-  if (bucket >= (nB << P.lg2)) return;
+  const uint32_t nB = 1u << hs.lgB;
+  if (bucket >= (nB << hs.lg2)) return;
   // the (sub-)bucket's records
-  const uint64_t* __restrict__ recs = P.lg2 == 0 ? B.rec : B.rec2;
-  const uint32_t rec0 = P.lg2 == 0 ? B.bstart[bucket] : B.bstart2[bucket];
-  const uint32_t rec1 = P.lg2 == 0 ? rec0 + B.bstart[nB + 1 + bucket] : B.bstart2[bucket + 1];
+  const uint64_t* __restrict__ recs = hs.lg2 == 0 ? B.rec : B.rec2;
+  const uint32_t rec0 = hs.lg2 == 0 ? B.bstart[bucket] : B.bstart2[bucket];
+  const uint32_t rec1 = hs.lg2 == 0 ? rec0 + B.bstart[nB + 1 + bucket] : B.bstart2[bucket + 1];
   const uint32_t cnt = rec1 - rec0;
   if (cnt == 0) return;
-  const int free_bits = 32 - P.lgB - P.lg2;  // hash bits below the (sub-)bucket's
+  const int free_bits = 32 - hs.lgB - hs.lg2;  // hash bits below the (sub-)bucket's
   const int max_lgR = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
   int lgR = 0;
   while (lgR < max_lgR && (cnt >> lgR) > kPartSlots / 2) ++lgR;

@@ -1,8 +1,13 @@
 // libsmfg wide path: fanouts above SMFG_MAX_FANOUT and SMFG_FANOUT_ALL, samples at exact block offsets.
+// count_rows / scan_count_tiles fix the offsets; then either the table strategy (sample_insert_wide,
+// flag_flat, scan_flat_tiles, assemble_flat) or the partition strategy (sample_wide, hist_flat,
+// scan_hist, scatter_flat, [split_buckets], dedup_buckets, flag_flat_part, scan_flat_tiles,
+// assemble_flat_part) turns the samples into local ids.
 #ifndef SMFG_KERNELS_WIDE_H_
 #define SMFG_KERNELS_WIDE_H_
 
 #include "device_common.h"
+#include "kernels_part.h"
 
 namespace smfg_dev {
 
@@ -22,9 +27,17 @@ __global__ void __launch_bounds__(kThreads) k_count_rows(const Launch P) {
     const int i = tile * kTileRows + threadIdx.x;
     uint32_t k = 0;
     if (i < n) {
-      const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
-      const int64_t a = P.indptr[v];
-      const uint32_t deg = static_cast<uint32_t>(P.indptr[v + 1] - a);
+      const int32_t id = B.node_ids[i];
+      int64_t a = 0;
+      uint32_t deg = 0;
+      // the seeds are caller data: none may index the graph unchecked (later hops only hold
+      // neighbour ids read from the graph)
+      if (P.h == 0 && (id < 0 || static_cast<int64_t>(id) >= P.num_nodes)) {
+        set_status(B, P.L, SMFG_ST_SEED_OUT_OF_RANGE);
+      } else {
+        a = P.indptr[id];
+        deg = static_cast<uint32_t>(P.indptr[id + 1] - a);
+      }
       k = (d < 0 || deg <= static_cast<uint32_t>(d)) ? deg : static_cast<uint32_t>(d);
       B.rowstart[i] = a;
       B.rowdeg[i] = deg;
@@ -63,8 +76,11 @@ __global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
   }
 }
 
-// One wave per destination; lane l of round r owns slot s = 64 r + l.
-__global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P) {
+// One wave per destination; lane l of round r owns slot s = 64 r + l.  INSERT: the sample goes
+// into the dedup table at once (table strategy); else only its node id is stored (partition
+// strategy).
+template <bool INSERT>
+__global__ void __launch_bounds__(kThreads) k_sample_wide(const Launch P) {
   __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (__any(status_of(B, P.L) != 0)) return;  // whole waves only: the lanes below cooperate
@@ -106,20 +122,237 @@ __global__ void __launch_bounds__(kThreads) k_sample_insert_wide(const Launch P)
         __builtin_amdgcn_wave_barrier();
       }
       if (active) {
-        const uint32_t g = static_cast<uint32_t>(P.indices[a + p]);
+        const uint32_t g = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + p)));
         const uint32_t pos = base + s;
-        uint32_t slot;
-        bool full;
-        const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
-        if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
-        uint32_t e = prev;  // see k_sample_insert for the three cases
-        if (prev > (kPend | pos)) {
-          e = kSlot | slot;
-          if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
+        if (INSERT) {
+          uint32_t slot;
+          bool full;
+          const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
+          if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
+          uint32_t e = prev;  // see k_sample_insert for the three cases
+          if (prev > (kPend | pos)) {
+            e = kSlot | slot;
+            if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
+          }
+          B.ent[pos] = e;
         }
-        B.ent[pos] = e;
         B.gsrc[pos] = static_cast<int32_t>(g);
       }
+    }
+  }
+}
+
+// ---- partition strategy over exact offsets ----------------------------------------------------
+// The records of a hop as one stream: element e < n is known node e, element n + pos the sample
+// at position pos.  A flat block owns kFlatBlock consecutive elements.
+__device__ __forceinline__ unsigned long long flat_record(const BatchCtx& B, uint32_t e, uint32_t n) {
+  if (e < n) return (static_cast<unsigned long long>(static_cast<uint32_t>(B.node_ids[e])) << 32) | e;
+  const uint32_t pos = e - n;
+  return (static_cast<unsigned long long>(static_cast<uint32_t>(B.gsrc[pos])) << 32) | (kPend | pos);
+}
+
+// Per flat block: records per bucket -> hist row.
+__global__ void __launch_bounds__(kThreads) k_hist_flat(const Launch P) {
+  __shared__ uint32_t hist[1 << kPartMaxLgB];
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const int blk = block_in_batch(P);
+  if (blk >= hop_blocks(P, B)) return;
+  const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
+  const uint32_t total = n + static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const int lgB = hop_shape(P, B).lgB;
+  const int nB = 1 << lgB;
+  for (int b = threadIdx.x; b < nB; b += kThreads) hist[b] = 0u;
+  __syncthreads();
+  const uint32_t e0 = static_cast<uint32_t>(blk) * kFlatBlock;
+  constexpr int U = 8;
+  for (uint32_t c0 = e0; c0 < e0 + kFlatBlock && c0 < total; c0 += kThreads * U) {
+    unsigned long long r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t e = c0 + u * kThreads + threadIdx.x;
+      r[u] = e < total ? flat_record(B, e, n) : kEmpty;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (r[u] != kEmpty) atomicAdd(&hist[part_bucket(static_cast<uint32_t>(r[u] >> 32), lgB)], 1u);
+  }
+  __syncthreads();
+  uint32_t* out = B.hist + static_cast<size_t>(blk) * nB;
+  for (int b = threadIdx.x; b < nB; b += kThreads) out[b] = hist[b];
+}
+
+// Records of a flat block -> their buckets, staged in LDS in rounds like k_scatter.
+__global__ void __launch_bounds__(kThreads) k_scatter_flat(const Launch P) {
+  __shared__ uint32_t gbase[1 << kPartMaxLgB];
+  __shared__ uint32_t cnt[1 << kPartMaxLgB];
+  __shared__ uint32_t lstart[1 << kPartMaxLgB];
+  __shared__ unsigned long long stage[kScatterRound];
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const int blk = block_in_batch(P);
+  if (blk >= hop_blocks(P, B)) return;
+  const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
+  const uint32_t total_e = n + static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const int lgB = hop_shape(P, B).lgB;
+  const int nB = 1 << lgB;
+  constexpr int per = (1 << kPartMaxLgB) / kThreads;
+  {
+    uint32_t sz[per];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      sz[u] = b < nB ? B.bstart[nB + 1 + b] : 0u;
+      mine += sz[u];
+    }
+    unsigned long long total;
+    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+    const uint32_t* offs = B.hist + static_cast<size_t>(blk) * nB;
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      if (b < nB) {
+        gbase[b] = pre + offs[b];
+        if (blk == 0) B.bstart[b] = pre;
+      }
+      pre += sz[u];
+    }
+    if (blk == 0 && threadIdx.x == 0) B.bstart[nB] = static_cast<uint32_t>(total);
+  }
+  const uint32_t e0 = static_cast<uint32_t>(blk) * kFlatBlock;
+  for (uint32_t c0 = e0; c0 < e0 + kFlatBlock && c0 < total_e; c0 += kScatterRound) {
+    __syncthreads();
+    for (int b = threadIdx.x; b < nB; b += kThreads) cnt[b] = 0u;
+    __syncthreads();
+    unsigned long long r[kScatterPer];
+    uint32_t bk[kScatterPer], rk[kScatterPer];
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u) {
+      const uint32_t e = c0 + u * kThreads + threadIdx.x;
+      r[u] = e < total_e ? flat_record(B, e, n) : kEmpty;
+    }
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u) {
+      bk[u] = 0u;
+      rk[u] = 0u;
+      if (r[u] != kEmpty) {
+        bk[u] = part_bucket(static_cast<uint32_t>(r[u] >> 32), lgB);
+        rk[u] = atomicAdd(&cnt[bk[u]], 1u);
+      }
+    }
+    __syncthreads();
+    uint32_t c[per];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      c[u] = b < nB ? cnt[b] : 0u;
+      mine += c[u];
+    }
+    unsigned long long total;
+    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      if (b < nB) lstart[b] = pre;
+      pre += c[u];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kScatterPer; ++u)
+      if (r[u] != kEmpty) stage[lstart[bk[u]] + rk[u]] = r[u];
+    __syncthreads();
+    const uint32_t staged = static_cast<uint32_t>(total);
+    for (uint32_t t = threadIdx.x; t < staged; t += kThreads) {
+      const unsigned long long x = stage[t];
+      const uint32_t b = part_bucket(static_cast<uint32_t>(x >> 32), lgB);
+      B.rec[gbase[b] + (t - lstart[b])] = x;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < per; ++u) {
+      const int b = threadIdx.x * per + u;
+      if (b < nB) gbase[b] += c[u];
+    }
+  }
+}
+
+// flag_flat for the entries dedup_buckets leaves (a sample whose gsrc entry still is a node id is a
+// first appearance): in-tile ranks, per-tile totals.
+__global__ void __launch_bounds__(kThreads) k_flag_flat_part(const Launch P) {
+  __shared__ unsigned long long lds[kThreads / 64];
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (block_has_status(B, P.L)) return;
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  for (uint32_t tile = block_in_batch(P); tile < tiles; tile += blocks_per_batch(P)) {
+    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
+    uint32_t first[4];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t pos = p0 + u;
+      first[u] = (pos < E && (static_cast<uint32_t>(B.gsrc[pos]) & kResolved) == 0u) ? 1u : 0u;
+      mine += first[u];
+    }
+    unsigned long long total;
+    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (p0 + u < E) B.rank[p0 + u] = pre;
+      pre += first[u];
+    }
+    if (threadIdx.x == 0) B.stile_sums[tile] = total;
+    __syncthreads();
+  }
+}
+
+// assemble_flat for those entries.
+__global__ void __launch_bounds__(kThreads) k_assemble_flat_part(const Launch P) {
+  const BatchCtx& B = P.b[batch_of_block(P)];
+  if (status_of(B, P.L) != 0) return;
+  const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
+  const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
+  const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  for (uint32_t tile = block_in_batch(P); tile < tiles; tile += blocks_per_batch(P)) {
+    const uint32_t tpre = n + static_cast<uint32_t>(B.stile_sums[tile]);
+    const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
+    uint32_t e[4], rk[4], q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t pos = p0 + u;
+      e[u] = pos < E ? static_cast<uint32_t>(B.gsrc[pos]) : kResolved;
+      rk[u] = pos < E ? B.rank[pos] : 0u;
+      q[u] = (e[u] & kPointer) == kPointer ? (e[u] & ~kPointer) : 0u;
+    }
+    // what the pointers name is fetched for all four samples before any is used
+    uint32_t qrank[4], qtile[4], qe[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      qrank[u] = B.rank[q[u]];
+      qtile[u] = static_cast<uint32_t>(B.stile_sums[q[u] / kWideTile]);
+      qe[u] = static_cast<uint32_t>(B.gsrc[q[u]]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t pos = p0 + u;
+      if (pos >= E) continue;
+      uint32_t local;
+      if ((e[u] & kResolved) == 0u) {  // first appearance
+        local = tpre + rk[u];
+        B.node_ids[local] = static_cast<int32_t>(e[u]);
+      } else if ((e[u] & kPointer) == kPointer) {
+        local = n + qtile[u] + qrank[u];
+        if ((qe[u] & kResolved) != 0u) {  // the named sample is not a first appearance: scratch disturbed
+          set_status(B, P.L, SMFG_ST_INTERNAL);
+          local = 0u;
+        }
+      } else {
+        local = e[u] & ~kPointer;
+      }
+      B.blk_indices[pos] = static_cast<int32_t>(local);
     }
   }
 }

@@ -145,6 +145,7 @@ struct smfg_workspace {
   int64_t bytes;
   // partition strategy (no dedup table) or table strategy; fixed when the workspace is planned
   bool part;
+  bool flat;             // partition strategy also over exact offsets (wide fanouts): rank, row starts etc. present
   int64_t rec_entries;   // capacity of rec: known nodes + samples of a hop
   int64_t hist_entries;  // capacity of hist: row blocks x buckets of a hop
   int split_lg;          // log2 of the most sub-buckets a hop needs (0: no hop splits its buckets)
@@ -311,14 +312,31 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
   ws->node_capacity = node_capacity;
   ws->slot_entries = slots > 0 ? slots : 1;
   ws->table_log2 = lg;
-  ws->part = !table_forced() &&
-             part_needs(max_seeds, L, fanouts, g->num_nodes, node_capacity, &ws->rec_entries, &ws->hist_entries,
-                        &ws->split_lg) &&
-             slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity) <= ws->slot_entries;
+  bool wide = false;
+  check_fanouts(L, fanouts, &wide);
+  if (wide && !table_forced()) {
+    // partition strategy over exact offsets: a hop holds at most node_capacity known nodes and
+    // slot_entries samples
+    ws->part = ws->flat = true;
+    ws->rec_entries = node_capacity + ws->slot_entries;
+    int lg = 0;
+    while (lg < kPartMaxLgB + kPartMaxLg2 && (ws->rec_entries >> lg) > kPartBucketRecords) ++lg;
+    const int lgB = lg < kPartMaxLgB ? lg : kPartMaxLgB;
+    ws->split_lg = lg > lgB ? lg : 0;
+    int64_t rows = (ws->rec_entries + kFlatBlock - 1) / kFlatBlock + 1;
+    if (rows < 520) rows = 520;  // a later call with fanouts up to SMFG_MAX_FANOUT uses row blocks instead
+    ws->hist_entries = rows << lgB;
+  } else {
+    ws->part = !table_forced() &&
+               part_needs(max_seeds, L, fanouts, g->num_nodes, node_capacity, &ws->rec_entries, &ws->hist_entries,
+                          &ws->split_lg) &&
+               slot_entries_needed(max_seeds, L, fanouts, g->num_nodes, node_capacity) <= ws->slot_entries;
+  }
   const int64_t tiles = (node_capacity + kTileRows - 1) / kTileRows + 1;
   ws->b_slot = align256(ws->slot_entries * 4);
   ws->b_row = align256((node_capacity + 4) * 4);
   ws->b_tiles = align256(tiles * 8);
+  ws->b_stiles = align256((ws->slot_entries / kWideTile + 2) * 8);
   if (ws->part) {
     ws->b_rec = align256(ws->rec_entries * 8);
     ws->b_hist = align256(ws->hist_entries * 4);
@@ -326,9 +344,9 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
     ws->b_bstart2 = ws->split_lg > 0 ? align256(((int64_t(1) << ws->split_lg) + 2) * 4) : 0;
     ws->bytes = ws->b_slot + 4 * ws->b_row + ws->b_tiles + (ws->split_lg > 0 ? 2 : 1) * ws->b_rec + ws->b_hist +
                 ws->b_bstart + ws->b_bstart2;
+    if (ws->flat) ws->bytes += ws->b_slot + 3 * ws->b_row + ws->b_stiles;
   } else {
     ws->b_table = align256((int64_t(1) << lg) * 8);
-    ws->b_stiles = align256((ws->slot_entries / kWideTile + 2) * 8);
     ws->bytes = ws->b_table + 4 * ws->b_slot + 8 * ws->b_row + ws->b_tiles + ws->b_stiles;
   }
   return SMFG_OK;
@@ -348,7 +366,13 @@ void bind_workspace(smfg_workspace* ws, void* base) {
     ws->bstart = reinterpret_cast<uint32_t*>(p); p += ws->b_bstart;
     if (ws->split_lg > 0) {
       ws->bstart2 = reinterpret_cast<uint32_t*>(p); p += ws->b_bstart2;
-      ws->rec2 = reinterpret_cast<uint64_t*>(p);
+      ws->rec2 = reinterpret_cast<uint64_t*>(p); p += ws->b_rec;
+    }
+    if (ws->flat) {
+      ws->rank = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
+      ws->rowstart = reinterpret_cast<int64_t*>(p); p += 2 * ws->b_row;
+      ws->rowdeg = reinterpret_cast<int32_t*>(p); p += ws->b_row;
+      ws->stile_sums = reinterpret_cast<uint64_t*>(p);
     }
     return;
   }
@@ -680,8 +704,21 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
   }
   if (!part && !table) return SMFG_ERR_INVALID_ARG;  // workspaces of one call must be planned alike
   HopPlan plan[SMFG_MAX_LAYERS];
-  if (part) {
-    if (wide) return SMFG_ERR_CAPACITY;  // such a workspace was planned for fanouts up to SMFG_MAX_FANOUT
+  HopPlan flat_plan = {0, 0, 0, 1};
+  if (part && wide) {
+    // exact offsets: every workspace must have been planned for wide fanouts; the shape of a hop
+    // is settled on the device, the host only bounds it by the roomiest workspace
+    int64_t bound = 1;
+    for (int b = 0; b < num_batches; ++b) {
+      if (!ws[b]->flat) return SMFG_ERR_CAPACITY;
+      if (ws[b]->rec_entries > bound) bound = ws[b]->rec_entries;
+    }
+    int lg = 0;
+    while (lg < kPartMaxLgB + kPartMaxLg2 && (bound >> lg) > kPartBucketRecords) ++lg;
+    flat_plan.lgB = lg < kPartMaxLgB ? lg : kPartMaxLgB;
+    flat_plan.lg2 = lg - flat_plan.lgB;
+    flat_plan.row_blocks = (bound + kFlatBlock - 1) / kFlatBlock;
+  } else if (part) {
     for (int h = 0; h < L; ++h) {
       plan[h] = plan_hop(max_n[h], fanouts[h]);
       const int64_t records = max_n[h] * (1 + fanouts[h]);
@@ -718,7 +755,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     }
     const int64_t rows = max_n[h];
     const unsigned tile_blocks = blocks_for(rows, kTileRows, kCap);
-    if (part) {
+    if (part && !wide) {
       P.lgB = plan[h].lgB;
       P.lg2 = plan[h].lg2;
       P.block_rows = plan[h].block_rows;
@@ -756,14 +793,51 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       int64_t samples = P.d < 0 ? max_entries : rows * P.d;  // upper bound of E_h
       if (samples > max_entries) samples = max_entries;
       const unsigned flat_blocks = blocks_for(samples, kWideTile, kCap);
+      const unsigned wave_blocks = blocks_for(rows, kThreads / 64, 2 * kCap);
       {
         StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
         k_count_rows<<<tile_blocks * G, kThreads, 0, st>>>(P);
         k_scan_count_tiles<<<G, kThreads, 0, st>>>(P);
       }
+      if (part) {
+        P.flat = 1;
+        P.lgB = flat_plan.lgB;
+        P.lg2 = flat_plan.lg2;
+        int64_t stream_bound = rows + samples;  // known nodes + samples of this hop, at most
+        const unsigned stream_blocks = blocks_for(stream_bound, kFlatBlock, 0x7FFFFFFFu / SMFG_MAX_BATCHES);
+        const unsigned buckets = 1u << P.lgB;
+        {
+          StageTimer t_(SMFG_STAGE_SAMPLE, st);
+          k_sample_wide<false><<<wave_blocks * G, kThreads, 0, st>>>(P);
+        }
+        {
+          StageTimer t_(SMFG_STAGE_PARTITION, st);
+          k_hist_flat<<<stream_blocks * G, kThreads, 0, st>>>(P);
+          k_scan_hist<<<((buckets + kScanCols - 1) / kScanCols) * G, kThreads, 0, st>>>(P);
+          k_scatter_flat<<<stream_blocks * G, kThreads, 0, st>>>(P);
+          if (P.lg2 > 0) k_split_buckets<<<buckets * G, kThreads, 0, st>>>(P);
+        }
+        {
+          StageTimer t_(SMFG_STAGE_DEDUP, st);
+          k_dedup_buckets<<<(buckets << P.lg2) * G, kThreads, 0, st>>>(P);
+        }
+        {
+          StageTimer t_(SMFG_STAGE_FLAG, st);
+          k_flag_flat_part<<<flat_blocks * G, kThreads, 0, st>>>(P);
+        }
+        {
+          StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
+          k_scan_flat_tiles<<<G, kThreads, 0, st>>>(P);
+        }
+        {
+          StageTimer t_(SMFG_STAGE_ASSEMBLE, st);
+          k_assemble_flat_part<<<flat_blocks * G, kThreads, 0, st>>>(P);
+        }
+        continue;
+      }
       {
         StageTimer t_(SMFG_STAGE_SAMPLE, st);
-        k_sample_insert_wide<<<blocks_for(rows, kThreads / 64, 2 * kCap) * G, kThreads, 0, st>>>(P);
+        k_sample_wide<true><<<wave_blocks * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_FLAG, st);
