@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # Small batches are bound by the latency of the chain of short kernels, so they take more batches
 # per set and two sampling streams; the largest batches fill the chip one at a time.
 LAUNCH_CONFIG = {"tiny": (4, 1, 2), "mid": (16, 2, 3), "large": (8, 1, 2), "papers": (8, 1, 2),
-                 "papers_infer": (1, 2, 3), "large_wide": (2, 1, 2), "large_all": (2, 1, 2)}
+                 "papers_infer": (1, 2, 3), "large_wide": (4, 2, 3), "large_all": (4, 2, 3)}
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 
 

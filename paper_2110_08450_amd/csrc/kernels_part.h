@@ -323,9 +323,11 @@ __global__ void __launch_bounds__(kThreads) k_split_buckets(const Launch P) {
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
   const HopShape hs = hop_shape(P, B);
-  const uint32_t b1 = static_cast<uint32_t>(block_in_batch(P));
   const uint32_t nB1 = 1u << hs.lgB;
-  if (hs.lg2 == 0 || b1 >= nB1) return;
+  if (hs.lg2 == 0) return;
+  for (uint32_t b1 = static_cast<uint32_t>(block_in_batch(P)); b1 < nB1;
+       b1 += static_cast<uint32_t>(blocks_per_batch(P))) {
+  __syncthreads();  // the previous bucket's last round has left the LDS arrays
   const int n2 = 1 << hs.lg2;
   const int shift = 32 - hs.lgB - hs.lg2;
   const uint32_t mask = static_cast<uint32_t>(n2 - 1);
@@ -423,6 +425,7 @@ __global__ void __launch_bounds__(kThreads) k_split_buckets(const Launch P) {
       if (b < n2) gbase[b] += c[u];
     }
   }
+  }
 }
 
 // One block per bucket.  All records of a node are in one bucket, so the bucket's table in LDS
@@ -437,17 +440,17 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
   const HopShape hs = hop_shape(P, B);
-  const uint32_t bucket = static_cast<uint32_t>(block_in_batch(P));
   const uint32_t nB = 1u << hs.lgB;
-  if (bucket >= (nB << hs.lg2)) return;
-  // the (sub-)bucket's records
   const uint64_t* __restrict__ recs = hs.lg2 == 0 ? B.rec : B.rec2;
+  const int free_bits = 32 - hs.lgB - hs.lg2;  // hash bits below the (sub-)bucket's
+  const int max_lgR = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
+  for (uint32_t bucket = static_cast<uint32_t>(block_in_batch(P)); bucket < (nB << hs.lg2);
+       bucket += static_cast<uint32_t>(blocks_per_batch(P))) {
+  // the (sub-)bucket's records
   const uint32_t rec0 = hs.lg2 == 0 ? B.bstart[bucket] : B.bstart2[bucket];
   const uint32_t rec1 = hs.lg2 == 0 ? rec0 + B.bstart[nB + 1 + bucket] : B.bstart2[bucket + 1];
   const uint32_t cnt = rec1 - rec0;
-  if (cnt == 0) return;
-  const int free_bits = 32 - hs.lgB - hs.lg2;  // hash bits below the (sub-)bucket's
-  const int max_lgR = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
+  if (cnt == 0) continue;
   int lgR = 0;
   while (lgR < max_lgR && (cnt >> lgR) > kPartSlots / 2) ++lgR;
   for (;;) {
@@ -540,6 +543,7 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
       break;
     }
     ++lgR;
+  }
   }
 }
 

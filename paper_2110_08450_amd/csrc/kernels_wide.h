@@ -76,67 +76,160 @@ __global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
   }
 }
 
-// One wave per destination; lane l of round r owns slot s = 64 r + l.  INSERT: the sample goes
-// into the dedup table at once (table strategy); else only its node id is stored (partition
-// strategy).
+// A wave takes kWideRows consecutive destinations: lane l first fetches the row record of
+// destination l (start, degree, sample count, block offset: coalesced, once per group of rows),
+// then the wave walks the rows, lane l of round r owning slot s = 64 r + l: first the rows that are
+// one plain round (whole row taken, at most 64 samples; several in flight), then the others one by
+// one.  INSERT: the sample goes into
+// the dedup table at once (table strategy); else only its node id is stored (partition strategy).
+constexpr int kWideRows = 16;
+
+// What happens to a drawn sample: recorded (partition strategy), or also inserted into the dedup
+// table right away (table strategy; see k_sample_insert for the three cases).
+template <bool INSERT>
+__device__ __forceinline__ void wide_emit(const Launch& P, const BatchCtx& B, uint32_t g, uint32_t pos) {
+  if (INSERT) {
+    uint32_t slot;
+    bool full;
+    const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
+    if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
+    uint32_t e = prev;
+    if (prev > (kPend | pos)) {
+      e = kSlot | slot;
+      if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
+    }
+    B.ent[pos] = e;
+  }
+  B.gsrc[pos] = static_cast<int32_t>(g);
+}
+
+// Floyd's subset algorithm for one destination with k > 32 slots, by one wave (lane l owns slots
+// l, l + 64, ...).  Slot s draws t_s in [0, j_s], j_s = deg - k + s, and takes t_s unless an
+// earlier slot holds that position, else j_s.  Settled without walking the slots one by one:
+// an earlier slot holds t_s exactly if (a) an earlier slot drew the same value - whether that slot
+// kept it or not, the value was in the set by then - or (b) t_s is the j of an earlier slot q (only
+// q = t_s - (deg - k) can be) and slot q took its j, i.e. was itself refused.  (a) needs no other
+// slot's outcome; (b) refers to one earlier slot.  So every slot is refused outright, accepted
+// outright, or "as slot q": chains of such references are shortcut by pointer jumping, at most
+// log2 k + 1 passes.  `draws` keeps the t_s, `picks` the states and in the end the positions p_s
+// (both LDS, k entries, private to the wave).
+__device__ __forceinline__ void floyd_positions(const Launch& P, const BatchCtx& B, uint32_t v, uint32_t deg,
+                                                uint32_t k, uint32_t* picks, uint32_t* draws) {
+  constexpr uint32_t kKnown = 0x80000000u, kRefused = 0x40000000u, kRefMask = 0x3FFFFFFFu;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t j0 = deg - k;
+  for (uint32_t s = lane; s < k; s += 64u) {
+    const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), s >> 2, B.key0, B.key1, s & 3u);
+    draws[s] = __umulhi(w, j0 + s + 1u);  // index in [0, j_s]
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const uint4* draws4 = reinterpret_cast<const uint4*>(draws);
+  for (uint32_t s0 = 0; s0 < k; s0 += 64u) {
+    const uint32_t s = s0 + lane;
+    const bool active = s < k;
+    const uint32_t t = active ? draws[s] : 0u;
+    bool dup = false;
+    const uint32_t upto = s0 + 64u < k ? s0 + 64u : k;
+    // every lane reads the same four draws at a time (a broadcast read); entries at or beyond s
+    // are masked out, so the read may run past k inside the array
+#pragma unroll 4
+    for (uint32_t q = 0; q + 1u < upto; q += 4u) {
+      const uint4 x = draws4[q >> 2];
+      dup = dup | ((q < s) & (x.x == t)) | ((q + 1u < s) & (x.y == t)) | ((q + 2u < s) & (x.z == t)) |
+            ((q + 3u < s) & (x.w == t));
+    }
+    const bool refers = !dup && t >= j0 && t - j0 < s;
+    if (active) picks[s] = dup ? (kKnown | kRefused) : (refers ? t - j0 : kKnown);
+  }
+  for (;;) {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    bool open = false;
+    for (uint32_t s = lane; s < k; s += 64u) {
+      const uint32_t st = picks[s];
+      if ((st & kKnown) == 0u) {
+        // as slot q: take its outcome if it has one, else refer to what it refers to (a word is read
+        // and written whole, and a state only ever moves forward along its chain, so the order in
+        // which lanes get here does not matter)
+        const uint32_t sq = picks[st & kRefMask];
+        picks[s] = (sq & kKnown) ? sq : (sq & kRefMask);
+        open = open || (sq & kKnown) == 0u;
+      }
+    }
+    if (__ballot(open) == 0ull) break;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  for (uint32_t s = lane; s < k; s += 64u) picks[s] = (picks[s] & kRefused) ? j0 + s : draws[s];
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 template <bool INSERT>
 __global__ void __launch_bounds__(kThreads) k_sample_wide(const Launch P) {
   __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
+  __shared__ __align__(16) uint32_t draws_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (__any(status_of(B, P.L) != 0)) return;  // whole waves only: the lanes below cooperate
   const int n = static_cast<int>(B.counts[P.h]);
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* picks = picks_lds[wave];
+  uint32_t* draws = draws_lds[wave];
   const int waves_total = blocks_per_batch(P) * (kThreads / 64);
-  for (int i = block_in_batch(P) * (kThreads / 64) + wave; i < n; i += waves_total) {
-    const uint32_t v = static_cast<uint32_t>(B.node_ids[i]);
-    const int64_t a = B.rowstart[i];
-    const uint32_t deg = static_cast<uint32_t>(B.rowdeg[i]);
-    const uint32_t k = static_cast<uint32_t>(B.rowk[i]);
-    const uint32_t base = static_cast<uint32_t>(B.tile_sums[i / kTileRows]) + static_cast<uint32_t>(B.rowoff[i]);
-    if (lane == 0) B.blk_indptr[i] = static_cast<int32_t>(base);
-    const bool floyd = deg > k;  // only then are positions drawn (k = fanout <= SMFG_MAX_WIDE_FANOUT)
-    for (uint32_t s0 = 0; s0 < k; s0 += 64) {
-      const uint32_t s = s0 + static_cast<uint32_t>(lane);
-      const bool active = s < k;
-      uint32_t p = s;  // whole row in CSR order when nothing is drawn
-      if (floyd) {
-        uint32_t t = 0, j = 0;
-        if (active) {
-          const uint32_t w = philox_word(v, static_cast<uint32_t>(P.h), s >> 2, B.key0, B.key1, s & 3u);
-          j = deg - k + s;
-          t = __umulhi(w, j + 1u);  // index in [0, j]
-        }
-        // Floyd's rule slot by slot; the array set is picks[0, s0) in LDS plus the lanes of this round
-        const uint32_t round = k - s0 < 64u ? k - s0 : 64u;
-        for (uint32_t q = 0; q < round; ++q) {
-          const uint32_t tq = __shfl(t, static_cast<int>(q), 64);
-          bool hit = static_cast<uint32_t>(lane) < q && p == tq;
-          for (uint32_t l = static_cast<uint32_t>(lane); l < s0; l += 64) hit = hit || picks[l] == tq;
-          const bool any = __ballot(hit) != 0ull;
-          if (static_cast<uint32_t>(lane) == q) p = any ? j : tq;
-        }
-        if (active) picks[s] = p;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // later rounds read all lanes' picks
-        __builtin_amdgcn_wave_barrier();
+  for (int i0 = (block_in_batch(P) * (kThreads / 64) + wave) * kWideRows; i0 < n; i0 += waves_total * kWideRows) {
+    const int il = i0 + lane;
+    uint32_t v_l = 0, deg_l = 0, k_l = 0, base_l = 0, a_lo = 0, a_hi = 0;
+    if (lane < kWideRows && il < n) {
+      v_l = static_cast<uint32_t>(B.node_ids[il]);
+      const int64_t a = B.rowstart[il];
+      a_lo = static_cast<uint32_t>(a);
+      a_hi = static_cast<uint32_t>(static_cast<uint64_t>(a) >> 32);
+      deg_l = static_cast<uint32_t>(B.rowdeg[il]);
+      k_l = static_cast<uint32_t>(B.rowk[il]);
+      base_l = static_cast<uint32_t>(B.tile_sums[il / kTileRows]) + static_cast<uint32_t>(B.rowoff[il]);
+      B.blk_indptr[il] = static_cast<int32_t>(base_l);
+    }
+    const int rows = n - i0 < kWideRows ? n - i0 : kWideRows;
+    static_assert(kWideRows % 4 == 0, "rows are walked four at a time");
+    for (int r0 = 0; r0 < rows; r0 += 4) {  // lanes beyond the last row hold k = 0
+      uint32_t g[4], pos[4];
+      bool on[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int r = r0 + u;
+        const int64_t a = static_cast<int64_t>((static_cast<uint64_t>(__shfl(a_hi, r, 64)) << 32) | __shfl(a_lo, r, 64));
+        const uint32_t deg = __shfl(deg_l, r, 64);
+        const uint32_t k = __shfl(k_l, r, 64);
+        pos[u] = __shfl(base_l, r, 64) + static_cast<uint32_t>(lane);
+        on[u] = deg == k && k <= 64u && static_cast<uint32_t>(lane) < k;
+        g[u] = on[u] ? static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + lane))) : 0u;
       }
-      if (active) {
-        const uint32_t g = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + p)));
-        const uint32_t pos = base + s;
-        if (INSERT) {
-          uint32_t slot;
-          bool full;
-          const uint32_t prev = table_insert_min(B, g, kPend | pos, slot, full);
-          if (full) set_status(B, P.L, SMFG_ST_TABLE_FULL);
-          uint32_t e = prev;  // see k_sample_insert for the three cases
-          if (prev > (kPend | pos)) {
-            e = kSlot | slot;
-            if (prev != 0xFFFFFFFFu) B.lostto[prev & ~kTagMask] = kPend | pos;
-          }
-          B.ent[pos] = e;
-        }
-        B.gsrc[pos] = static_cast<int32_t>(g);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (on[u]) wide_emit<INSERT>(P, B, g[u], pos[u]);
+    }
+    for (int r = 0; r < rows; ++r) {
+      const uint32_t v = __shfl(v_l, r, 64);
+      const int64_t a = static_cast<int64_t>((static_cast<uint64_t>(__shfl(a_hi, r, 64)) << 32) | __shfl(a_lo, r, 64));
+      const uint32_t deg = __shfl(deg_l, r, 64);
+      const uint32_t k = __shfl(k_l, r, 64);
+      const uint32_t base = __shfl(base_l, r, 64);
+      const bool floyd = deg > k;  // only then are positions drawn (k = fanout <= SMFG_MAX_WIDE_FANOUT)
+      if (!floyd && k <= 64u) continue;  // done above
+      if (floyd) floyd_positions(P, B, v, deg, k, picks, draws);
+      for (uint32_t s0 = 0; s0 < k; s0 += 128) {  // two rounds at a time: both reads leave before either result is used
+        const uint32_t sa = s0 + static_cast<uint32_t>(lane), sb = sa + 64u;
+        uint32_t ga = 0, gb = 0;
+        if (sa < k) ga = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + (floyd ? picks[sa] : sa))));
+        if (sb < k) gb = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + (floyd ? picks[sb] : sb))));
+        if (sa < k) wide_emit<INSERT>(P, B, ga, base + sa);  // whole row in CSR order when nothing is drawn
+        if (sb < k) wide_emit<INSERT>(P, B, gb, base + sb);
+      }
+      if (floyd) {  // the next row's draws must not overwrite picks a lane has yet to read
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
     }
   }
@@ -156,12 +249,13 @@ __global__ void __launch_bounds__(kThreads) k_hist_flat(const Launch P) {
   __shared__ uint32_t hist[1 << kPartMaxLgB];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
-  const int blk = block_in_batch(P);
-  if (blk >= hop_blocks(P, B)) return;
   const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
   const uint32_t total = n + static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const int lgB = hop_shape(P, B).lgB;
   const int nB = 1 << lgB;
+  const int blocks = hop_blocks(P, B);
+  for (int blk = block_in_batch(P); blk < blocks; blk += blocks_per_batch(P)) {
+  __syncthreads();
   for (int b = threadIdx.x; b < nB; b += kThreads) hist[b] = 0u;
   __syncthreads();
   const uint32_t e0 = static_cast<uint32_t>(blk) * kFlatBlock;
@@ -180,6 +274,7 @@ __global__ void __launch_bounds__(kThreads) k_hist_flat(const Launch P) {
   __syncthreads();
   uint32_t* out = B.hist + static_cast<size_t>(blk) * nB;
   for (int b = threadIdx.x; b < nB; b += kThreads) out[b] = hist[b];
+  }
 }
 
 // Records of a flat block -> their buckets, staged in LDS in rounds like k_scatter.
@@ -191,13 +286,14 @@ __global__ void __launch_bounds__(kThreads) k_scatter_flat(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
-  const int blk = block_in_batch(P);
-  if (blk >= hop_blocks(P, B)) return;
   const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
   const uint32_t total_e = n + static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const int lgB = hop_shape(P, B).lgB;
   const int nB = 1 << lgB;
   constexpr int per = (1 << kPartMaxLgB) / kThreads;
+  const int blocks = hop_blocks(P, B);
+  for (int blk = block_in_batch(P); blk < blocks; blk += blocks_per_batch(P)) {
+  __syncthreads();  // the previous flat block's last round has left the LDS arrays
   {
     uint32_t sz[per];
     uint32_t mine = 0;
@@ -277,6 +373,7 @@ __global__ void __launch_bounds__(kThreads) k_scatter_flat(const Launch P) {
       if (b < nB) gbase[b] += c[u];
     }
   }
+  }
 }
 
 // flag_flat for the entries dedup_buckets leaves (a sample whose gsrc entry still is a node id is a
@@ -328,12 +425,11 @@ __global__ void __launch_bounds__(kThreads) k_assemble_flat_part(const Launch P)
       q[u] = (e[u] & kPointer) == kPointer ? (e[u] & ~kPointer) : 0u;
     }
     // what the pointers name is fetched for all four samples before any is used
-    uint32_t qrank[4], qtile[4], qe[4];
+    uint32_t qrank[4], qtile[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       qrank[u] = B.rank[q[u]];
       qtile[u] = static_cast<uint32_t>(B.stile_sums[q[u] / kWideTile]);
-      qe[u] = static_cast<uint32_t>(B.gsrc[q[u]]);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -344,11 +440,7 @@ __global__ void __launch_bounds__(kThreads) k_assemble_flat_part(const Launch P)
         local = tpre + rk[u];
         B.node_ids[local] = static_cast<int32_t>(e[u]);
       } else if ((e[u] & kPointer) == kPointer) {
-        local = n + qtile[u] + qrank[u];
-        if ((qe[u] & kResolved) != 0u) {  // the named sample is not a first appearance: scratch disturbed
-          set_status(B, P.L, SMFG_ST_INTERNAL);
-          local = 0u;
-        }
+        local = n + qtile[u] + qrank[u];  // a pointer always names a first appearance
       } else {
         local = e[u] & ~kPointer;
       }

@@ -773,7 +773,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       }
       {
         StageTimer t_(SMFG_STAGE_DEDUP, st);
-        k_dedup_buckets<<<(buckets << P.lg2) * G, kThreads, 0, st>>>(P);
+        k_dedup_buckets<<<blocks_for(int64_t(buckets) << P.lg2, 1, 2 * kCap) * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_FLAG, st);
@@ -793,7 +793,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       int64_t samples = P.d < 0 ? max_entries : rows * P.d;  // upper bound of E_h
       if (samples > max_entries) samples = max_entries;
       const unsigned flat_blocks = blocks_for(samples, kWideTile, kCap);
-      const unsigned wave_blocks = blocks_for(rows, kThreads / 64, 2 * kCap);
+      const unsigned wave_blocks = blocks_for(rows, kWideRows * (kThreads / 64), 2 * kCap);
       {
         StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
         k_count_rows<<<tile_blocks * G, kThreads, 0, st>>>(P);
@@ -804,7 +804,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
         P.lgB = flat_plan.lgB;
         P.lg2 = flat_plan.lg2;
         int64_t stream_bound = rows + samples;  // known nodes + samples of this hop, at most
-        const unsigned stream_blocks = blocks_for(stream_bound, kFlatBlock, 0x7FFFFFFFu / SMFG_MAX_BATCHES);
+        const unsigned stream_blocks = blocks_for(stream_bound, kFlatBlock, kCap);
         const unsigned buckets = 1u << P.lgB;
         {
           StageTimer t_(SMFG_STAGE_SAMPLE, st);
@@ -819,7 +819,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
         }
         {
           StageTimer t_(SMFG_STAGE_DEDUP, st);
-          k_dedup_buckets<<<(buckets << P.lg2) * G, kThreads, 0, st>>>(P);
+          k_dedup_buckets<<<blocks_for(int64_t(buckets) << P.lg2, 1, 2 * kCap) * G, kThreads, 0, st>>>(P);
         }
         {
           StageTimer t_(SMFG_STAGE_FLAG, st);
