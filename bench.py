@@ -256,31 +256,47 @@ def main():
     args.depth = args.depth or max(cfg[2], args.sample_streams + 1)
     G = max(1, min(args.batches_per_call, smfg.MAX_BATCHES))
     L = len(w.fanouts)
+    K = max(1, args.steps)      # a pass = exactly K batches
+    W = max(0, args.warmup)
+
+    def set_bounds(first, n):
+        """Cuts batches first .. first+n-1 into launch sets of equal size (give or take one batch):
+        G batches each, or more - up to the library's limit of 16 - when n is not a multiple of G,
+        because a short last set would run against a full one in the other stream and lose the overlap."""
+        if n <= 0:
+            return [first]
+        n_sets = max(1, (n + smfg.MAX_BATCHES - 1) // smfg.MAX_BATCHES, n // G)
+        return [first + (n * i) // n_sets for i in range(n_sets + 1)]
+
+    def largest_set(n):
+        b = set_bounds(0, n)
+        return max([y - x for x, y in zip(b[:-1], b[1:])] + [0])
     g = smfg.graph_create(graph.indptr, graph.indices, feat)
     pipe = None
     wide = any(d < 0 or d > smfg.MAX_FANOUT for d in w.fanouts)
     scap = min(graph.num_edges, (1 << 30) - 1) if wide else 0   # a hop never has more samples than the graph has edges
     if args.pipeline:
         from paper_2110_08450_amd.pipeline import BatchPipeline
-        pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=G, sample_capacity=scap,
-                             depth=max(2, args.depth, args.sample_streams + 1), sample_streams=args.sample_streams)
+        depth_ = max(2, args.depth, args.sample_streams + 1)
+        Gbuf = max(G, largest_set(K), largest_set(max(W, depth_ * G)))     # batches a buffer set must hold
+        pipe = BatchPipeline(g, w.fanouts, w.batch_size, batches_per_set=Gbuf, sample_capacity=scap,
+                             depth=depth_, sample_streams=args.sample_streams)
         streams, wss, outs = pipe.s_samples + [pipe.s_gather], pipe.wss, pipe.outs
         S = len(streams)
     else:
         S = max(1, args.streams)
+        Gbuf = max(G, largest_set(K), largest_set(max(W, S * G)))
         streams = [torch.cuda.Stream() for _ in range(S)]
-        wss = [[smfg.workspace_create(g, w.batch_size, w.fanouts, 0, scap) for _ in range(G)] for _ in range(S)]
-        outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(G)] for _ in range(S)]
+        wss = [[smfg.workspace_create(g, w.batch_size, w.fanouts, 0, scap) for _ in range(Gbuf)] for _ in range(S)]
+        outs = [[smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(Gbuf)] for _ in range(S)]
     row_bytes = g.row_bytes
 
-    K = max(1, args.steps)      # a pass = exactly K batches; its last launch set may be partial
-    W = max(0, args.warmup)
     keys = [synth.batch_rng_key(w, i) for i in range(len(batches))]
     depth = pipe.depth if pipe is not None else S
     # Per-batch counts live in a ring of rows: a buffer set is reused `depth` launch sets later (the
     # pipeline's events order that), a ring slot one launch set after that.
     ring = depth + 1
-    counts_ring = torch.zeros((ring * G, 2 * L + 2), dtype=torch.int64, device=dev)
+    counts_ring = torch.zeros((ring * Gbuf, 2 * L + 2), dtype=torch.int64, device=dev)
     stride = counts_ring.stride(0) * 8
 
     last_call = {}   # buffer set -> (first batch index, batches, ring slot) of the last launch set that used it
@@ -288,15 +304,16 @@ def main():
 
     def run_calls(first, n):
         """Issues batches first .. first+n-1 (indices modulo the number of seed batches)."""
-        for c in range(first, first + n, G):
-            k = min(G, first + n - c)
+        bounds = set_bounds(first, n)
+        for c, c_next in zip(bounds[:-1], bounds[1:]):
+            k = c_next - c
             s_no = sets_issued[0]
             sets_issued[0] += 1
             q = s_no % depth
             slot = s_no % ring
             last_call[q] = (c, k, slot)
             idx = [(c + b) % len(batches) for b in range(k)]
-            base = counts_ring.data_ptr() + slot * G * stride
+            base = counts_ring.data_ptr() + slot * Gbuf * stride
             if pipe is not None:
                 def point_counts(os_, base=base):
                     for b, o in enumerate(os_):
@@ -316,7 +333,7 @@ def main():
         run_calls(c, k)
         torch.cuda.synchronize()
         slot = (sets_issued[0] - 1) % ring
-        cnt += counts_ring[slot * G:slot * G + k].cpu().tolist()
+        cnt += counts_ring[slot * Gbuf:slot * Gbuf + k].cpu().tolist()
     assert all(c[2 * L + 1] == 0 for c in cnt), "a batch reported a device status"
     n_final = sum(c[L] for c in cnt)
     edges = sum(sum(c[L + 1:2 * L + 1]) for c in cnt)
@@ -332,7 +349,7 @@ def main():
     torch.cuda.synchronize()
     probe = time.perf_counter() - t0
     passes = args.passes if args.passes > 0 else int(min(max(5, 0.6 / max(probe, 1e-6)), 400, max(5, 30.0 / max(probe, 1e-6))))
-    sets_per_pass = (K + G - 1) // G
+    sets_per_pass = len(set_bounds(0, K)) - 1
 
     # Timed region: `passes` passes of K batches each, issued back to back (no host synchronisation
     # between them), bracketed by device synchronisations.  A pass ends when the last stream has
@@ -412,7 +429,7 @@ def main():
             for b in range(k_set):
                 o, c = outs[q][b], cnt_q[b]
                 n_dst, e_last = c[L - 1], c[2 * L]
-                cview = counts_ring[slot_q * G + b]
+                cview = counts_ring[slot_q * Gbuf + b]
                 smfg.mean_aggregate(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.indptr[L - 1].numel() - 1, o.features,
                                     agg_out, stream=streams[0])
                 agg_bytes += e_last * row_bytes + 4 * e_last + 4 * (n_dst + 1) + 4 * w.feat_dim * n_dst
@@ -436,7 +453,7 @@ def main():
                 for b in range(k_set):
                     o, c = outs[q][b], cnt_q[b]
                     n_dst, e_last = c[L - 1], c[2 * L]
-                    cview = counts_ring[slot_q * G + b]
+                    cview = counts_ring[slot_q * Gbuf + b]
                     smfg.sage_layer(o.indptr[L - 1], o.indices[L - 1], cview[L - 1:L], o.indptr[L - 1].numel() - 1,
                                     o.features, lw, lb, True, lay_out, stream=streams[0])
                     lay_bytes += (e_last + n_dst) * row_bytes + 4 * e_last + 4 * (n_dst + 1) + 2 * hid * n_dst
@@ -465,7 +482,8 @@ def main():
                    "region_s_host_clock": region_s, "region_batches_per_s": passes * K / region_s},
         "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {graph.num_edges} directed edges, "
                                f"features {w.feat_dim}x{str(w.feat_dtype).split('.')[-1]}, fanouts {list(w.fanouts)}, "
-                               f"batch {w.batch_size}", "batches_per_call": G, "streams": S, "pipeline": bool(args.pipeline),
+                               f"batch {w.batch_size}", "batches_per_call": G, "launch_sets_of_a_pass": [y - x for x, y in zip(set_bounds(0, K)[:-1], set_bounds(0, K)[1:])][:8],
+                   "streams": S, "pipeline": bool(args.pipeline),
                    "sample_streams": args.sample_streams if args.pipeline else None,
                    "buffer_sets": depth,
                    "row_stride_bytes": int(feat.stride(0) * feat.element_size()),
