@@ -484,6 +484,7 @@ def main():
                                f"features {w.feat_dim}x{str(w.feat_dtype).split('.')[-1]}, fanouts {list(w.fanouts)}, "
                                f"batch {w.batch_size}", "batches_per_call": G, "launch_sets_of_a_pass": [y - x for x, y in zip(set_bounds(0, K)[:-1], set_bounds(0, K)[1:])][:8],
                    "streams": S, "pipeline": bool(args.pipeline),
+                   "dedup_strategy": wss[0][0].strategy,
                    "sample_streams": args.sample_streams if args.pipeline else None,
                    "buffer_sets": depth,
                    "row_stride_bytes": int(feat.stride(0) * feat.element_size()),

@@ -151,6 +151,21 @@ int smfg_workspace_create_sized(smfg_workspace_t **out, const smfg_graph_t *g, i
 int smfg_workspace_destroy(smfg_workspace_t *ws);
 /* Bytes of device scratch the workspace holds (0 for NULL). */
 int64_t smfg_workspace_bytes(const smfg_workspace_t *ws);
+/*
+ * How calls on this workspace remove duplicates and number new nodes (the global-to-local map of
+ * procedure OneHopMFG); both give the same, serial-order result.
+ *   SMFG_STRATEGY_PARTITION  the records of a hop (known nodes, samples) are grouped by node hash
+ *                            and every group is settled in a hash table in on-chip memory: no
+ *                            table in device memory, no device-wide atomics.  The default.
+ *   SMFG_STRATEGY_TABLE      one open-addressing table in device memory per batch, claimed with
+ *                            atomics.  Chosen when no hop of the planned size reaches 32768
+ *                            records (fewer launches per hop; such calls are launch bound).
+ * The environment variable SMFG_DEDUP=table or =partition, read when a workspace is created,
+ * overrides the choice (for measurements and tests).  Returns -1 for NULL.
+ */
+#define SMFG_STRATEGY_TABLE 0
+#define SMFG_STRATEGY_PARTITION 1
+int smfg_workspace_strategy(const smfg_workspace_t *ws);
 
 /* Output of one batch.  Every pointer is a caller-owned DEVICE buffer. */
 typedef struct {

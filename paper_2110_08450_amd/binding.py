@@ -25,13 +25,14 @@ ERR_INVALID_ARG, ERR_NULL_PTR, ERR_BAD_FANOUT, ERR_TOO_MANY_LAYERS = -1, -2, -3,
 ERR_TOO_MANY_SEEDS, ERR_OOM, ERR_CAPACITY, ERR_BAD_GRAPH, ERR_HIP_BASE = -5, -6, -7, -8, -1000
 ST_NODE_CAPACITY, ST_EDGE_CAPACITY, ST_TABLE_FULL, ST_SEED_OUT_OF_RANGE, ST_DUPLICATE_SEED = 1, 2, 3, 4, 5
 ST_INTERNAL = 6
+STRATEGY_TABLE, STRATEGY_PARTITION = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsmfg.so")
 
 EXPORTS = [
     "smfg_graph_create", "smfg_graph_destroy", "smfg_graph_validate", "smfg_graph_set_labels", "smfg_bounds",
     "smfg_workspace_create", "smfg_workspace_create_sized",
-    "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_sample_mfg", "smfg_sample_mfg_many",
+    "smfg_workspace_destroy", "smfg_workspace_bytes", "smfg_workspace_strategy", "smfg_sample_mfg", "smfg_sample_mfg_many",
     "smfg_sample_mfg_static",
     "smfg_gather_rows", "smfg_gather_many", "smfg_mean_aggregate", "smfg_sage_layer", "smfg_sage_pack_weights",
     "smfg_sage_packed_bytes", "smfg_read_counts", "smfg_strerror", "smfg_profile_begin", "smfg_profile_end",
@@ -80,6 +81,7 @@ def lib() -> ctypes.CDLL:
         L.smfg_workspace_destroy.argtypes = [vp]
         L.smfg_workspace_bytes.argtypes = [vp]
         L.smfg_workspace_bytes.restype = i64
+        L.smfg_workspace_strategy.argtypes = [vp]
         L.smfg_sample_mfg.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32), i32, u64,
                                       ctypes.POINTER(_Output), vp]
         L.smfg_sample_mfg_static.argtypes = [vp, vp, i32, ctypes.POINTER(i32), i32, u64, ctypes.POINTER(_Output), vp]
@@ -196,6 +198,11 @@ class Workspace:
     @property
     def nbytes(self) -> int:
         return int(lib().smfg_workspace_bytes(self.handle))
+
+    @property
+    def strategy(self) -> str:
+        """'partition' or 'table': how calls on this workspace dedup a hop."""
+        return "partition" if lib().smfg_workspace_strategy(self.handle) == STRATEGY_PARTITION else "table"
 
     def __del__(self):
         if getattr(self, "handle", None):

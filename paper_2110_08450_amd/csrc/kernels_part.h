@@ -476,9 +476,13 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
           const uint32_t hsh = node * kPartHash;
           if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
           uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
+          // A plain read first: a node sampled thousands of times (a hub) would otherwise queue
+          // thousands of atomics on one LDS word, while most of its records only need to see that
+          // a smaller value is there already.  Slots never lose their node, values only fall.
           uint32_t probes = 0;
           for (; probes < kPartSlots; ++probes) {
-            const unsigned long long old = atomicCAS(&tab[sl], kEmpty, mine[u]);
+            unsigned long long old = tab[sl];
+            if (old == kEmpty) old = atomicCAS(&tab[sl], kEmpty, mine[u]);
             if (old == kEmpty) break;
             if (static_cast<uint32_t>(old >> 32) == node) {
               if (old > mine[u]) atomicMin(&tab[sl], mine[u]);

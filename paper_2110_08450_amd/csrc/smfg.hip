@@ -580,6 +580,10 @@ int smfg_workspace_destroy(smfg_workspace_t* ws) {
 
 int64_t smfg_workspace_bytes(const smfg_workspace_t* ws) { return ws ? ws->bytes : 0; }
 
+int smfg_workspace_strategy(const smfg_workspace_t* ws) {
+  return ws ? (ws->part ? SMFG_STRATEGY_PARTITION : SMFG_STRATEGY_TABLE) : -1;
+}
+
 int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, const int32_t* const* d_seeds,
                          const int32_t* num_seeds, const int32_t* fanouts, int32_t L, const uint64_t* rng_keys,
                          const smfg_output_t* outs, int32_t num_batches, void* hip_stream) {

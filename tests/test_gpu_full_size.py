@@ -17,6 +17,7 @@ def _check_batches(w, graph, feat, g, orc, batches, batch_ids, per_call, sample_
     rows are checked against torch indexing of the same table with the oracle's node list."""
     L = len(w.fanouts)
     wss = [smfg.workspace_create(g, w.batch_size, w.fanouts, 0, sample_capacity) for _ in range(per_call)]
+    assert all(ws.strategy == "partition" for ws in wss)      # every benchmark workload but `tiny` takes it
     outs = [smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(per_call)]
     for c0 in range(0, len(batch_ids), per_call):
         ids = batch_ids[c0:c0 + per_call]
@@ -177,6 +178,7 @@ def _full_pass(w, graph, feat, g, base_oracle, threads=12, per_call=8):
             pool_oracles.put(o)
 
     wss = [smfg.workspace_create(g, w.batch_size, w.fanouts) for _ in range(per_call)]
+    assert all(ws.strategy == "partition" for ws in wss)
     outs = [smfg.alloc_output(g, w.batch_size, w.fanouts) for _ in range(per_call)]
     total_nodes = total_edges = 0
     with ThreadPoolExecutor(threads) as ex:

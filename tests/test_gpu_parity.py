@@ -62,8 +62,10 @@ def assert_same(res, ref, L):
 
 
 def run_one(gg, seeds_np, fanouts, key, **cap):
+    import os
     seeds = torch.from_numpy(np.ascontiguousarray(seeds_np, dtype=np.int32)).to(DEV)
     ws = smfg.workspace_create(gg.g, len(seeds_np), fanouts)
+    assert ws.strategy == os.environ["SMFG_DEDUP"]      # the strategy under test is the one that runs
     out = smfg.alloc_output(gg.g, len(seeds_np), fanouts, **cap)
     smfg.sample_mfg(gg.g, ws, seeds, fanouts, key, out)
     return fetch(out, len(fanouts))
