@@ -185,18 +185,123 @@ __global__ void __launch_bounds__(kThreads) k_scan_hist(const Launch P) {
   }
 }
 
-// Records of the block's destinations -> their buckets.  The records of a round (up to
-// kScatterRound: the block's known nodes first, then its samples in position order) are counted
-// per bucket, ordered by bucket in LDS and written out in that order, so that the records a bucket
-// receives from this block leave as one run of consecutive addresses.
-constexpr int kScatterPer = 8;                          // stream elements per thread and round
+// ---- records to buckets, in rounds staged through LDS ------------------------------------------
+// A block that moves records to buckets takes them in rounds of kScatterRound (kScatterPer per
+// thread): the round's records are counted per bucket (each gets its rank within its bucket by an
+// LDS atomicAdd), the counts are scanned, the records are put in bucket order into a staging
+// array in LDS and written out in that order, so that what a bucket receives from a round leaves
+// as one run of consecutive addresses.  gbase[b] is where the block's next record of bucket b goes.
+constexpr int kScatterPer = 8;
 constexpr int kScatterRound = kScatterPer * kThreads;
+constexpr int kStageBuckets = 1 << (kPartMaxLgB > kPartMaxLg2 ? kPartMaxLgB : kPartMaxLg2);
+constexpr int kStagePer = kStageBuckets / kThreads;  // buckets per thread in the block scans
+
+struct StageLds {
+  uint32_t gbase[kStageBuckets];
+  uint32_t cnt[kStageBuckets];
+  uint32_t lstart[kStageBuckets];
+  unsigned long long stage[kScatterRound];
+  unsigned long long scan[kThreads / 64];
+};
+
+// gbase[b] <- first + exclusive scan of sizes[b] (+ offs[b] if given), b < nb; returns the total
+// of the sizes.  `write_starts`, if given, also receives first + the exclusive scan.
+template <typename SizeOf, typename OffOf, typename StartTo>
+__device__ __forceinline__ uint32_t stage_set_bases(StageLds& L, int nb, uint32_t first, SizeOf size_of, OffOf off_of,
+                                                     StartTo start_to) {
+  uint32_t sz[kStagePer];
+  uint32_t mine = 0;
+#pragma unroll
+  for (int u = 0; u < kStagePer; ++u) {
+    const int b = threadIdx.x * kStagePer + u;
+    sz[u] = b < nb ? size_of(b) : 0u;
+    mine += sz[u];
+  }
+  unsigned long long total;
+  uint32_t pre = first + static_cast<uint32_t>(block_exscan(mine, L.scan, total));
+#pragma unroll
+  for (int u = 0; u < kStagePer; ++u) {
+    const int b = threadIdx.x * kStagePer + u;
+    if (b < nb) {
+      L.gbase[b] = pre + off_of(b);
+      start_to(b, pre);
+    }
+    pre += sz[u];
+  }
+  __syncthreads();
+  return static_cast<uint32_t>(total);
+}
+
+// One round: r[u] are this thread's records (kEmpty = none), bucket_of maps a node to its bucket
+// in [0, nb).  All threads of the block call.
+template <typename BucketOf>
+__device__ __forceinline__ void stage_round(StageLds& L, int nb, const unsigned long long (&r)[kScatterPer],
+                                            BucketOf bucket_of, uint64_t* __restrict__ dst) {
+  __syncthreads();  // the previous round has been written out
+  for (int b = threadIdx.x; b < nb; b += kThreads) L.cnt[b] = 0u;
+  __syncthreads();
+  uint32_t bk[kScatterPer], rk[kScatterPer];
+#pragma unroll
+  for (int u = 0; u < kScatterPer; ++u) {
+    bk[u] = 0u;
+    rk[u] = 0u;
+    if (r[u] != kEmpty) {
+      bk[u] = bucket_of(static_cast<uint32_t>(r[u] >> 32));
+      rk[u] = atomicAdd(&L.cnt[bk[u]], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t c[kStagePer];
+  uint32_t mine = 0;
+#pragma unroll
+  for (int u = 0; u < kStagePer; ++u) {
+    const int b = threadIdx.x * kStagePer + u;
+    c[u] = b < nb ? L.cnt[b] : 0u;
+    mine += c[u];
+  }
+  unsigned long long total;
+  uint32_t pre = static_cast<uint32_t>(block_exscan(mine, L.scan, total));
+#pragma unroll
+  for (int u = 0; u < kStagePer; ++u) {
+    const int b = threadIdx.x * kStagePer + u;
+    if (b < nb) L.lstart[b] = pre;
+    pre += c[u];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kScatterPer; ++u)
+    if (r[u] != kEmpty) L.stage[L.lstart[bk[u]] + rk[u]] = r[u];
+  __syncthreads();
+  const uint32_t staged = static_cast<uint32_t>(total);
+  for (uint32_t t = threadIdx.x; t < staged; t += kThreads) {
+    const unsigned long long x = L.stage[t];
+    const uint32_t b = bucket_of(static_cast<uint32_t>(x >> 32));
+    dst[L.gbase[b] + (t - L.lstart[b])] = x;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kStagePer; ++u) {
+    const int b = threadIdx.x * kStagePer + u;
+    if (b < nb) L.gbase[b] += c[u];
+  }
+}
+
+// The first record of every bucket (exclusive scan of the bucket sizes k_scan_hist left) plus this
+// block's offset within each bucket; block 0 also stores the bucket starts for k_dedup_buckets.
+__device__ __forceinline__ void stage_bucket_bases(StageLds& L, const BatchCtx& B, int nB, int blk) {
+  const uint32_t* offs = B.hist + static_cast<size_t>(blk) * nB;
+  const uint32_t total = stage_set_bases(
+      L, nB, 0u, [&](int b) { return B.bstart[nB + 1 + b]; }, [&](int b) { return offs[b]; },
+      [&](int b, uint32_t start) {
+        if (blk == 0) B.bstart[b] = start;
+      });
+  if (blk == 0 && threadIdx.x == 0) B.bstart[nB] = total;
+}
+
+// Records of the block's destinations (its known nodes first, then its samples in position
+// order) -> their buckets.
 __global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
-  __shared__ uint32_t gbase[1 << kPartMaxLgB];   // where this block's next record of a bucket goes
-  __shared__ uint32_t cnt[1 << kPartMaxLgB];     // records of the round per bucket
-  __shared__ uint32_t lstart[1 << kPartMaxLgB];  // their exclusive scan: first staging slot of a bucket
-  __shared__ unsigned long long stage[kScatterRound];
-  __shared__ unsigned long long lds[kThreads / 64];
+  __shared__ StageLds L;
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
   const int blk = block_in_batch(P);
@@ -205,40 +310,13 @@ __global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
   if (r0 >= n) return;
   const int r1 = r0 + P.block_rows < n ? r0 + P.block_rows : n;
   const int nB = 1 << P.lgB;
-  constexpr int per = (1 << kPartMaxLgB) / kThreads;  // buckets per thread in the scans
-  // first record of every bucket: exclusive scan of the bucket sizes
-  {
-    uint32_t sz[per];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      sz[u] = b < nB ? B.bstart[nB + 1 + b] : 0u;
-      mine += sz[u];
-    }
-    unsigned long long total;
-    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
-    const uint32_t* offs = B.hist + static_cast<size_t>(blk) * nB;
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      if (b < nB) {
-        gbase[b] = pre + offs[b];
-        if (blk == 0) B.bstart[b] = pre;
-      }
-      pre += sz[u];
-    }
-    if (blk == 0 && threadIdx.x == 0) B.bstart[nB] = static_cast<uint32_t>(total);
-  }
+  stage_bucket_bases(L, B, nB, blk);
   const uint32_t d = static_cast<uint32_t>(P.d);
   const DivD div(d);
   const uint32_t known = static_cast<uint32_t>(r1 - r0);
   const uint32_t pos0 = static_cast<uint32_t>(r0) * d;
   const uint32_t stream = known + known * d;  // known nodes, then the padded sample positions
   for (uint32_t c0 = 0; c0 < stream; c0 += kScatterRound) {
-    __syncthreads();  // gbase complete / previous round written out
-    for (int b = threadIdx.x; b < nB; b += kThreads) cnt[b] = 0u;
-    __syncthreads();
     unsigned long long rec[kScatterPer];
     uint32_t k[kScatterPer], sl[kScatterPer], g[kScatterPer];
 #pragma unroll
@@ -257,179 +335,71 @@ __global__ void __launch_bounds__(kThreads) k_scatter(const Launch P) {
         g[u] = static_cast<uint32_t>(B.gsrc[pos0 + (e - known)]);
       }
     }
-    uint32_t bk[kScatterPer], rk[kScatterPer];
 #pragma unroll
     for (int u = 0; u < kScatterPer; ++u) {
       const uint32_t e = c0 + u * kThreads + threadIdx.x;
       rec[u] = kEmpty;
-      bk[u] = 0u;
-      rk[u] = 0u;
       if (e < stream && sl[u] < k[u]) {
         // a known node (destination i has local id i), or a sample: tag | position
         const uint32_t val = e < known ? static_cast<uint32_t>(r0) + e : (kPend | (pos0 + (e - known)));
         rec[u] = (static_cast<unsigned long long>(g[u]) << 32) | val;
-        bk[u] = part_bucket(g[u], P.lgB);
-        rk[u] = atomicAdd(&cnt[bk[u]], 1u);
       }
     }
-    __syncthreads();
-    {
-      uint32_t c[per];
-      uint32_t mine = 0;
-#pragma unroll
-      for (int u = 0; u < per; ++u) {
-        const int b = threadIdx.x * per + u;
-        c[u] = b < nB ? cnt[b] : 0u;
-        mine += c[u];
-      }
-      unsigned long long total;
-      uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
-#pragma unroll
-      for (int u = 0; u < per; ++u) {
-        const int b = threadIdx.x * per + u;
-        if (b < nB) lstart[b] = pre;
-        pre += c[u];
-      }
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < kScatterPer; ++u)
-        if (rec[u] != kEmpty) stage[lstart[bk[u]] + rk[u]] = rec[u];
-      __syncthreads();
-      const uint32_t staged = static_cast<uint32_t>(total);
-      for (uint32_t t = threadIdx.x; t < staged; t += kThreads) {
-        const unsigned long long r = stage[t];
-        const uint32_t b = part_bucket(static_cast<uint32_t>(r >> 32), P.lgB);
-        B.rec[gbase[b] + (t - lstart[b])] = r;
-      }
-      __syncthreads();
-#pragma unroll
-      for (int u = 0; u < per; ++u) {
-        const int b = threadIdx.x * per + u;
-        if (b < nB) gbase[b] += c[u];
-      }
-    }
+    stage_round(L, nB, rec, [&](uint32_t node) { return part_bucket(node, P.lgB); }, B.rec);
   }
 }
 
-// One block per bucket: the bucket's records, ordered by the lg2 hash bits below the bucket's,
-// go to the same range of rec2; the sub-buckets' first records go to bstart2.  Counting pass, then
-// rounds of kScatterRound records staged in LDS like in k_scatter.
+// Grid-stride over the buckets: a bucket's records, ordered by the lg2 hash bits below the
+// bucket's, go to the same range of rec2; the sub-buckets' first records go to bstart2.  A counting
+// pass over the bucket, then the staged rounds.
 __global__ void __launch_bounds__(kThreads) k_split_buckets(const Launch P) {
-  __shared__ uint32_t gbase[1 << kPartMaxLg2];
-  __shared__ uint32_t cnt[1 << kPartMaxLg2];
-  __shared__ uint32_t lstart[1 << kPartMaxLg2];
-  __shared__ unsigned long long stage[kScatterRound];
-  __shared__ unsigned long long lds[kThreads / 64];
+  __shared__ StageLds L;
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
   const HopShape hs = hop_shape(P, B);
-  const uint32_t nB1 = 1u << hs.lgB;
   if (hs.lg2 == 0) return;
-  for (uint32_t b1 = static_cast<uint32_t>(block_in_batch(P)); b1 < nB1;
-       b1 += static_cast<uint32_t>(blocks_per_batch(P))) {
-  __syncthreads();  // the previous bucket's last round has left the LDS arrays
+  const uint32_t nB1 = 1u << hs.lgB;
   const int n2 = 1 << hs.lg2;
   const int shift = 32 - hs.lgB - hs.lg2;
   const uint32_t mask = static_cast<uint32_t>(n2 - 1);
-  const uint32_t rec0 = B.bstart[b1];
-  const uint32_t rec1 = rec0 + B.bstart[nB1 + 1 + b1];
-  constexpr int per = (1 << kPartMaxLg2) / kThreads;
-  for (int b = threadIdx.x; b < n2; b += kThreads) cnt[b] = 0u;
-  __syncthreads();
-  for (uint32_t c0 = rec0; c0 < rec1; c0 += kScatterRound) {
-    unsigned long long r[kScatterPer];
+  const auto sub_of = [&](uint32_t node) { return ((node * kPartHash) >> shift) & mask; };
+  for (uint32_t b1 = static_cast<uint32_t>(block_in_batch(P)); b1 < nB1;
+       b1 += static_cast<uint32_t>(blocks_per_batch(P))) {
+    const uint32_t rec0 = B.bstart[b1];
+    const uint32_t rec1 = rec0 + B.bstart[nB1 + 1 + b1];
+    __syncthreads();  // the previous bucket is done with the LDS arrays
+    for (int b = threadIdx.x; b < n2; b += kThreads) L.cnt[b] = 0u;
+    __syncthreads();
+    for (uint32_t c0 = rec0; c0 < rec1; c0 += kScatterRound) {
+      unsigned long long r[kScatterPer];
 #pragma unroll
-    for (int u = 0; u < kScatterPer; ++u) {
-      const uint32_t q = c0 + u * kThreads + threadIdx.x;
-      r[u] = q < rec1 ? B.rec[q] : kEmpty;
-    }
-#pragma unroll
-    for (int u = 0; u < kScatterPer; ++u)
-      if (r[u] != kEmpty) atomicAdd(&cnt[((static_cast<uint32_t>(r[u] >> 32) * kPartHash) >> shift) & mask], 1u);
-  }
-  __syncthreads();
-  {
-    uint32_t c[per];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      c[u] = b < n2 ? cnt[b] : 0u;
-      mine += c[u];
-    }
-    unsigned long long total;
-    uint32_t pre = rec0 + static_cast<uint32_t>(block_exscan(mine, lds, total));
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      if (b < n2) {
-        gbase[b] = pre;
-        B.bstart2[(static_cast<size_t>(b1) << hs.lg2) + b] = pre;
+      for (int u = 0; u < kScatterPer; ++u) {
+        const uint32_t q = c0 + u * kThreads + threadIdx.x;
+        r[u] = q < rec1 ? B.rec[q] : kEmpty;
       }
-      pre += c[u];
+#pragma unroll
+      for (int u = 0; u < kScatterPer; ++u)
+        if (r[u] != kEmpty) atomicAdd(&L.cnt[sub_of(static_cast<uint32_t>(r[u] >> 32))], 1u);
     }
+    __syncthreads();
+    stage_set_bases(
+        L, n2, rec0, [&](int b) { return L.cnt[b]; }, [](int) { return 0u; },
+        [&](int b, uint32_t start) { B.bstart2[(static_cast<size_t>(b1) << hs.lg2) + b] = start; });
     if (b1 == nB1 - 1 && threadIdx.x == 0) B.bstart2[static_cast<size_t>(nB1) << hs.lg2] = rec1;
-  }
-  for (uint32_t c0 = rec0; c0 < rec1; c0 += kScatterRound) {
-    __syncthreads();
-    for (int b = threadIdx.x; b < n2; b += kThreads) cnt[b] = 0u;
-    __syncthreads();
-    unsigned long long r[kScatterPer];
-    uint32_t bk[kScatterPer], rk[kScatterPer];
+    for (uint32_t c0 = rec0; c0 < rec1; c0 += kScatterRound) {
+      unsigned long long r[kScatterPer];
 #pragma unroll
-    for (int u = 0; u < kScatterPer; ++u) {
-      const uint32_t q = c0 + u * kThreads + threadIdx.x;
-      r[u] = q < rec1 ? B.rec[q] : kEmpty;
-    }
-#pragma unroll
-    for (int u = 0; u < kScatterPer; ++u) {
-      bk[u] = 0u;
-      rk[u] = 0u;
-      if (r[u] != kEmpty) {
-        bk[u] = ((static_cast<uint32_t>(r[u] >> 32) * kPartHash) >> shift) & mask;
-        rk[u] = atomicAdd(&cnt[bk[u]], 1u);
+      for (int u = 0; u < kScatterPer; ++u) {
+        const uint32_t q = c0 + u * kThreads + threadIdx.x;
+        r[u] = q < rec1 ? B.rec[q] : kEmpty;
       }
+      stage_round(L, n2, r, sub_of, B.rec2);
     }
-    __syncthreads();
-    uint32_t c[per];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      c[u] = b < n2 ? cnt[b] : 0u;
-      mine += c[u];
-    }
-    unsigned long long total;
-    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      if (b < n2) lstart[b] = pre;
-      pre += c[u];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < kScatterPer; ++u)
-      if (r[u] != kEmpty) stage[lstart[bk[u]] + rk[u]] = r[u];
-    __syncthreads();
-    const uint32_t staged = static_cast<uint32_t>(total);
-    for (uint32_t t = threadIdx.x; t < staged; t += kThreads) {
-      const unsigned long long x = stage[t];
-      const uint32_t b = ((static_cast<uint32_t>(x >> 32) * kPartHash) >> shift) & mask;
-      B.rec2[gbase[b] + (t - lstart[b])] = x;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      if (b < n2) gbase[b] += c[u];
-    }
-  }
   }
 }
 
-// One block per bucket.  All records of a node are in one bucket, so the bucket's table in LDS
-// sees every occurrence of its nodes.  A bucket with more records than the table takes is
+// Grid-stride over the (sub-)buckets, a block at a time.  All records of a node are in one bucket,
+// so the bucket's table in LDS sees every occurrence of its nodes.  A bucket with more records than the table takes is
 // handled in 2^lgR rounds, round r taking the nodes whose next lgR hash bits equal r; should a
 // round still overflow (skewed bits), the bucket starts over with one more bit.  With
 // 32 - lgB - lgR <= kPartTableLg bits left every node of a round has a slot of its own (the hash
@@ -446,57 +416,22 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
   const int max_lgR = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
   for (uint32_t bucket = static_cast<uint32_t>(block_in_batch(P)); bucket < (nB << hs.lg2);
        bucket += static_cast<uint32_t>(blocks_per_batch(P))) {
-  // the (sub-)bucket's records
-  const uint32_t rec0 = hs.lg2 == 0 ? B.bstart[bucket] : B.bstart2[bucket];
-  const uint32_t rec1 = hs.lg2 == 0 ? rec0 + B.bstart[nB + 1 + bucket] : B.bstart2[bucket + 1];
-  const uint32_t cnt = rec1 - rec0;
-  if (cnt == 0) continue;
-  int lgR = 0;
-  while (lgR < max_lgR && (cnt >> lgR) > kPartSlots / 2) ++lgR;
-  for (;;) {
-    bool failed = false;
-    const int rem = free_bits - lgR;  // hash bits below the round's
-    const uint32_t rounds = 1u << lgR;
-    for (uint32_t round = 0; round < rounds && !failed; ++round) {
-      for (uint32_t q = threadIdx.x; q < kPartSlots; q += kThreads) tab[q] = kEmpty;
-      if (threadIdx.x == 0) overflow_lds = 0;
-      __syncthreads();
-      constexpr int U = 8;  // records in flight per thread
-      for (uint32_t c0 = rec0; c0 < rec1; c0 += kThreads * U) {
-        unsigned long long mine[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const uint32_t r = c0 + u * kThreads + threadIdx.x;
-          mine[u] = r < rec1 ? recs[r] : kEmpty;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          if (mine[u] == kEmpty) continue;
-          const uint32_t node = static_cast<uint32_t>(mine[u] >> 32);
-          const uint32_t hsh = node * kPartHash;
-          if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
-          uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
-          // A plain read first: a node sampled thousands of times (a hub) would otherwise queue
-          // thousands of atomics on one LDS word, while most of its records only need to see that
-          // a smaller value is there already.  Slots never lose their node, values only fall.
-          uint32_t probes = 0;
-          for (; probes < kPartSlots; ++probes) {
-            unsigned long long old = tab[sl];
-            if (old == kEmpty) old = atomicCAS(&tab[sl], kEmpty, mine[u]);
-            if (old == kEmpty) break;
-            if (static_cast<uint32_t>(old >> 32) == node) {
-              if (old > mine[u]) atomicMin(&tab[sl], mine[u]);
-              break;
-            }
-            sl = (sl + 1u) & (kPartSlots - 1u);
-          }
-          if (probes == kPartSlots) overflow_lds = 1;
-        }
-      }
-      __syncthreads();
-      failed = overflow_lds != 0;
-      if (!failed) {
-        constexpr int U = 8;
+    // the (sub-)bucket's records
+    const uint32_t rec0 = hs.lg2 == 0 ? B.bstart[bucket] : B.bstart2[bucket];
+    const uint32_t rec1 = hs.lg2 == 0 ? rec0 + B.bstart[nB + 1 + bucket] : B.bstart2[bucket + 1];
+    const uint32_t cnt = rec1 - rec0;
+    if (cnt == 0) continue;
+    int lgR = 0;
+    while (lgR < max_lgR && (cnt >> lgR) > kPartSlots / 2) ++lgR;
+    for (;;) {
+      bool failed = false;
+      const int rem = free_bits - lgR;  // hash bits below the round's
+      const uint32_t rounds = 1u << lgR;
+      for (uint32_t round = 0; round < rounds && !failed; ++round) {
+        for (uint32_t q = threadIdx.x; q < kPartSlots; q += kThreads) tab[q] = kEmpty;
+        if (threadIdx.x == 0) overflow_lds = 0;
+        __syncthreads();
+        constexpr int U = 8;  // records in flight per thread
         for (uint32_t c0 = rec0; c0 < rec1; c0 += kThreads * U) {
           unsigned long long mine[U];
 #pragma unroll
@@ -508,46 +443,81 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
           for (int u = 0; u < U; ++u) {
             if (mine[u] == kEmpty) continue;
             const uint32_t node = static_cast<uint32_t>(mine[u] >> 32);
-            const uint32_t val = static_cast<uint32_t>(mine[u]);
             const uint32_t hsh = node * kPartHash;
             if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
             uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
-            uint32_t least = 0u;
+            // A plain read first: a node sampled thousands of times (a hub) would otherwise queue
+            // thousands of atomics on one LDS word, while most of its records only need to see that
+            // a smaller value is there already.  Slots never lose their node, values only fall.
             uint32_t probes = 0;
             for (; probes < kPartSlots; ++probes) {
-              const unsigned long long t = tab[sl];
-              if (static_cast<uint32_t>(t >> 32) == node) {
-                least = static_cast<uint32_t>(t);
+              unsigned long long old = tab[sl];
+              if (old == kEmpty) old = atomicCAS(&tab[sl], kEmpty, mine[u]);
+              if (old == kEmpty) break;
+              if (static_cast<uint32_t>(old >> 32) == node) {
+                if (old > mine[u]) atomicMin(&tab[sl], mine[u]);
                 break;
               }
               sl = (sl + 1u) & (kPartSlots - 1u);
             }
-            if (probes == kPartSlots) {  // every inserted node is found again
-              set_status(B, P.L, SMFG_ST_INTERNAL);
-              continue;
+            if (probes == kPartSlots) overflow_lds = 1;
+          }
+        }
+        __syncthreads();
+        failed = overflow_lds != 0;
+        if (!failed) {
+          constexpr int U = 8;
+          for (uint32_t c0 = rec0; c0 < rec1; c0 += kThreads * U) {
+            unsigned long long mine[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              const uint32_t r = c0 + u * kThreads + threadIdx.x;
+              mine[u] = r < rec1 ? recs[r] : kEmpty;
             }
-            if (val < kPend) {
-              // a known node: two of them with one id can only be a repeated seed
-              if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
-            } else {
-              // least < kPend: the node's final local id; least == val: this sample is the node's
-              // first appearance (entry stays); else least names the position of the first appearance
-              if (least != val)
-                B.gsrc[val & ~kTagMask] = static_cast<int32_t>(least < kPend ? (kResolved | least)
-                                                                             : (kPointer | (least & ~kTagMask)));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              if (mine[u] == kEmpty) continue;
+              const uint32_t node = static_cast<uint32_t>(mine[u] >> 32);
+              const uint32_t val = static_cast<uint32_t>(mine[u]);
+              const uint32_t hsh = node * kPartHash;
+              if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
+              uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
+              uint32_t least = 0u;
+              uint32_t probes = 0;
+              for (; probes < kPartSlots; ++probes) {
+                const unsigned long long t = tab[sl];
+                if (static_cast<uint32_t>(t >> 32) == node) {
+                  least = static_cast<uint32_t>(t);
+                  break;
+                }
+                sl = (sl + 1u) & (kPartSlots - 1u);
+              }
+              if (probes == kPartSlots) {  // every inserted node is found again
+                set_status(B, P.L, SMFG_ST_INTERNAL);
+                continue;
+              }
+              if (val < kPend) {
+                // a known node: two of them with one id can only be a repeated seed
+                if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
+              } else {
+                // least < kPend: the node's final local id; least == val: this sample is the node's
+                // first appearance (entry stays); else least names the position of the first appearance
+                if (least != val)
+                  B.gsrc[val & ~kTagMask] = static_cast<int32_t>(least < kPend ? (kResolved | least)
+                                                                               : (kPointer | (least & ~kTagMask)));
+              }
             }
           }
         }
+        __syncthreads();
       }
-      __syncthreads();
+      if (!failed) break;
+      if (lgR >= max_lgR) {  // cannot overflow with a slot per node
+        if (threadIdx.x == 0) set_status(B, P.L, SMFG_ST_INTERNAL);
+        break;
+      }
+      ++lgR;
     }
-    if (!failed) break;
-    if (lgR >= max_lgR) {  // cannot overflow with a slot per node
-      if (threadIdx.x == 0) set_status(B, P.L, SMFG_ST_INTERNAL);
-      break;
-    }
-    ++lgR;
-  }
   }
 }
 

@@ -255,124 +255,51 @@ __global__ void __launch_bounds__(kThreads) k_hist_flat(const Launch P) {
   const int nB = 1 << lgB;
   const int blocks = hop_blocks(P, B);
   for (int blk = block_in_batch(P); blk < blocks; blk += blocks_per_batch(P)) {
-  __syncthreads();
-  for (int b = threadIdx.x; b < nB; b += kThreads) hist[b] = 0u;
-  __syncthreads();
-  const uint32_t e0 = static_cast<uint32_t>(blk) * kFlatBlock;
-  constexpr int U = 8;
-  for (uint32_t c0 = e0; c0 < e0 + kFlatBlock && c0 < total; c0 += kThreads * U) {
-    unsigned long long r[U];
+    __syncthreads();
+    for (int b = threadIdx.x; b < nB; b += kThreads) hist[b] = 0u;
+    __syncthreads();
+    const uint32_t e0 = static_cast<uint32_t>(blk) * kFlatBlock;
+    constexpr int U = 8;
+    for (uint32_t c0 = e0; c0 < e0 + kFlatBlock && c0 < total; c0 += kThreads * U) {
+      unsigned long long r[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t e = c0 + u * kThreads + threadIdx.x;
-      r[u] = e < total ? flat_record(B, e, n) : kEmpty;
+      for (int u = 0; u < U; ++u) {
+        const uint32_t e = c0 + u * kThreads + threadIdx.x;
+        r[u] = e < total ? flat_record(B, e, n) : kEmpty;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (r[u] != kEmpty) atomicAdd(&hist[part_bucket(static_cast<uint32_t>(r[u] >> 32), lgB)], 1u);
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (r[u] != kEmpty) atomicAdd(&hist[part_bucket(static_cast<uint32_t>(r[u] >> 32), lgB)], 1u);
-  }
-  __syncthreads();
-  uint32_t* out = B.hist + static_cast<size_t>(blk) * nB;
-  for (int b = threadIdx.x; b < nB; b += kThreads) out[b] = hist[b];
+    __syncthreads();
+    uint32_t* out = B.hist + static_cast<size_t>(blk) * nB;
+    for (int b = threadIdx.x; b < nB; b += kThreads) out[b] = hist[b];
   }
 }
 
-// Records of a flat block -> their buckets, staged in LDS in rounds like k_scatter.
+// Records of a flat block -> their buckets, in the staged rounds of k_scatter.
 __global__ void __launch_bounds__(kThreads) k_scatter_flat(const Launch P) {
-  __shared__ uint32_t gbase[1 << kPartMaxLgB];
-  __shared__ uint32_t cnt[1 << kPartMaxLgB];
-  __shared__ uint32_t lstart[1 << kPartMaxLgB];
-  __shared__ unsigned long long stage[kScatterRound];
-  __shared__ unsigned long long lds[kThreads / 64];
+  __shared__ StageLds L;
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
   const uint32_t n = static_cast<uint32_t>(B.counts[P.h]);
   const uint32_t total_e = n + static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const int lgB = hop_shape(P, B).lgB;
   const int nB = 1 << lgB;
-  constexpr int per = (1 << kPartMaxLgB) / kThreads;
   const int blocks = hop_blocks(P, B);
   for (int blk = block_in_batch(P); blk < blocks; blk += blocks_per_batch(P)) {
-  __syncthreads();  // the previous flat block's last round has left the LDS arrays
-  {
-    uint32_t sz[per];
-    uint32_t mine = 0;
+    __syncthreads();  // the previous flat block is done with the LDS arrays
+    stage_bucket_bases(L, B, nB, blk);
+    const uint32_t e0 = static_cast<uint32_t>(blk) * kFlatBlock;
+    for (uint32_t c0 = e0; c0 < e0 + kFlatBlock && c0 < total_e; c0 += kScatterRound) {
+      unsigned long long r[kScatterPer];
 #pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      sz[u] = b < nB ? B.bstart[nB + 1 + b] : 0u;
-      mine += sz[u];
-    }
-    unsigned long long total;
-    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
-    const uint32_t* offs = B.hist + static_cast<size_t>(blk) * nB;
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      if (b < nB) {
-        gbase[b] = pre + offs[b];
-        if (blk == 0) B.bstart[b] = pre;
+      for (int u = 0; u < kScatterPer; ++u) {
+        const uint32_t e = c0 + u * kThreads + threadIdx.x;
+        r[u] = e < total_e ? flat_record(B, e, n) : kEmpty;
       }
-      pre += sz[u];
+      stage_round(L, nB, r, [&](uint32_t node) { return part_bucket(node, lgB); }, B.rec);
     }
-    if (blk == 0 && threadIdx.x == 0) B.bstart[nB] = static_cast<uint32_t>(total);
-  }
-  const uint32_t e0 = static_cast<uint32_t>(blk) * kFlatBlock;
-  for (uint32_t c0 = e0; c0 < e0 + kFlatBlock && c0 < total_e; c0 += kScatterRound) {
-    __syncthreads();
-    for (int b = threadIdx.x; b < nB; b += kThreads) cnt[b] = 0u;
-    __syncthreads();
-    unsigned long long r[kScatterPer];
-    uint32_t bk[kScatterPer], rk[kScatterPer];
-#pragma unroll
-    for (int u = 0; u < kScatterPer; ++u) {
-      const uint32_t e = c0 + u * kThreads + threadIdx.x;
-      r[u] = e < total_e ? flat_record(B, e, n) : kEmpty;
-    }
-#pragma unroll
-    for (int u = 0; u < kScatterPer; ++u) {
-      bk[u] = 0u;
-      rk[u] = 0u;
-      if (r[u] != kEmpty) {
-        bk[u] = part_bucket(static_cast<uint32_t>(r[u] >> 32), lgB);
-        rk[u] = atomicAdd(&cnt[bk[u]], 1u);
-      }
-    }
-    __syncthreads();
-    uint32_t c[per];
-    uint32_t mine = 0;
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      c[u] = b < nB ? cnt[b] : 0u;
-      mine += c[u];
-    }
-    unsigned long long total;
-    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      if (b < nB) lstart[b] = pre;
-      pre += c[u];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < kScatterPer; ++u)
-      if (r[u] != kEmpty) stage[lstart[bk[u]] + rk[u]] = r[u];
-    __syncthreads();
-    const uint32_t staged = static_cast<uint32_t>(total);
-    for (uint32_t t = threadIdx.x; t < staged; t += kThreads) {
-      const unsigned long long x = stage[t];
-      const uint32_t b = part_bucket(static_cast<uint32_t>(x >> 32), lgB);
-      B.rec[gbase[b] + (t - lstart[b])] = x;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < per; ++u) {
-      const int b = threadIdx.x * per + u;
-      if (b < nB) gbase[b] += c[u];
-    }
-  }
   }
 }
 
