@@ -33,7 +33,9 @@ struct BatchCtx {
   uint64_t* tile_sums;   // per tile: (edges << 32 | new nodes), later their exclusive scan
   int64_t* rowstart;     // wide path: first CSR position of the destination's row
   int32_t* rowdeg;       // wide path: degree of the destination
-  uint32_t* rank;        // wide path: new nodes of the sample's tile before this sample
+  uint32_t* rank;        // wide path, table strategy: new nodes of the sample's tile before this sample
+  uint4* grp;            // wide path, partition strategy: per 64 samples (.x, .y) first-appearance bits,
+                         // .z new nodes of the tile before the group
   uint64_t* stile_sums;  // wide path: per sample tile, new nodes, later their exclusive scan
   int32_t* blk_indptr;   // hop h
   int32_t* blk_indices;  // hop h

@@ -304,33 +304,42 @@ __global__ void __launch_bounds__(kThreads) k_scatter_flat(const Launch P) {
 }
 
 // flag_flat for the entries dedup_buckets leaves (a sample whose gsrc entry still is a node id is a
-// first appearance): in-tile ranks, per-tile totals.
+// first appearance).  Instead of a rank per sample, every group of 64 consecutive samples gets one
+// 16-byte record: the 64 first-appearance bits and the number of new nodes of the tile before the
+// group.  For a hop of millions of samples that is about a megabyte, which stays in the L2, so the
+// lookups of the samples that repeat a node (scattered over the hop) do not go to memory.
 __global__ void __launch_bounds__(kThreads) k_flag_flat_part(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (block_has_status(B, P.L)) return;
   const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
+  const int sub = threadIdx.x & 15;  // 16 threads x 4 samples = one group of 64
   for (uint32_t tile = block_in_batch(P); tile < tiles; tile += blocks_per_batch(P)) {
     const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
-    uint32_t first[4];
-    uint32_t mine = 0;
+    uint32_t nibble = 0;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t pos = p0 + u;
-      first[u] = (pos < E && (static_cast<uint32_t>(B.gsrc[pos]) & kResolved) == 0u) ? 1u : 0u;
-      mine += first[u];
+      if (pos < E && (static_cast<uint32_t>(B.gsrc[pos]) & kResolved) == 0u) nibble |= 1u << u;
     }
     unsigned long long total;
-    uint32_t pre = static_cast<uint32_t>(block_exscan(mine, lds, total));
+    const uint32_t pre = static_cast<uint32_t>(block_exscan(__popc(nibble), lds, total));
+    // the 16 nibbles of a group, OR-ed over its lanes
+    unsigned long long bits = static_cast<unsigned long long>(nibble) << (4 * sub);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (p0 + u < E) B.rank[p0 + u] = pre;
-      pre += first[u];
-    }
+    for (int o = 1; o < 16; o <<= 1) bits |= __shfl_xor(bits, o, 64);
+    if (sub == 0 && p0 < E)
+      B.grp[p0 >> 6] = make_uint4(static_cast<uint32_t>(bits), static_cast<uint32_t>(bits >> 32), pre, 0u);
     if (threadIdx.x == 0) B.stile_sums[tile] = total;
     __syncthreads();
   }
+}
+
+// New nodes of the hop before the sample at position q (a first appearance or not).
+__device__ __forceinline__ uint32_t flat_rank(const uint4 g, uint32_t tile_before, uint32_t q) {
+  const unsigned long long bits = (static_cast<unsigned long long>(g.y) << 32) | g.x;
+  return tile_before + g.z + __popcll(bits & ((1ull << (q & 63u)) - 1ull));
 }
 
 // assemble_flat for those entries.
@@ -341,21 +350,23 @@ __global__ void __launch_bounds__(kThreads) k_assemble_flat_part(const Launch P)
   const uint32_t E = static_cast<uint32_t>(B.counts[P.L + 1 + P.h]);
   const uint32_t tiles = (E + kWideTile - 1) / kWideTile;
   for (uint32_t tile = block_in_batch(P); tile < tiles; tile += blocks_per_batch(P)) {
-    const uint32_t tpre = n + static_cast<uint32_t>(B.stile_sums[tile]);
+    const uint32_t tpre = static_cast<uint32_t>(B.stile_sums[tile]);
     const uint32_t p0 = tile * kWideTile + threadIdx.x * 4;
-    uint32_t e[4], rk[4], q[4];
+    if (p0 >= E) continue;
+    const uint4 own = B.grp[p0 >> 6];  // the thread's four samples share a group
+    uint32_t e[4], q[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t pos = p0 + u;
       e[u] = pos < E ? static_cast<uint32_t>(B.gsrc[pos]) : kResolved;
-      rk[u] = pos < E ? B.rank[pos] : 0u;
-      q[u] = (e[u] & kPointer) == kPointer ? (e[u] & ~kPointer) : 0u;
+      q[u] = (e[u] & kPointer) == kPointer ? (e[u] & ~kPointer) : p0;
     }
     // what the pointers name is fetched for all four samples before any is used
-    uint32_t qrank[4], qtile[4];
+    uint4 qg[4];
+    uint32_t qtile[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      qrank[u] = B.rank[q[u]];
+      qg[u] = B.grp[q[u] >> 6];
       qtile[u] = static_cast<uint32_t>(B.stile_sums[q[u] / kWideTile]);
     }
 #pragma unroll
@@ -364,10 +375,10 @@ __global__ void __launch_bounds__(kThreads) k_assemble_flat_part(const Launch P)
       if (pos >= E) continue;
       uint32_t local;
       if ((e[u] & kResolved) == 0u) {  // first appearance
-        local = tpre + rk[u];
+        local = n + flat_rank(own, tpre, pos);
         B.node_ids[local] = static_cast<int32_t>(e[u]);
       } else if ((e[u] & kPointer) == kPointer) {
-        local = n + qtile[u] + qrank[u];  // a pointer always names a first appearance
+        local = n + flat_rank(qg[u], qtile[u], q[u]);  // a pointer always names a first appearance
       } else {
         local = e[u] & ~kPointer;
       }
@@ -376,6 +387,7 @@ __global__ void __launch_bounds__(kThreads) k_assemble_flat_part(const Launch P)
   }
 }
 
+// ---- table strategy over exact offsets ---------------------------------------------------------
 // Flat over the samples: first appearances, their in-tile ranks, per-tile totals.
 __global__ void __launch_bounds__(kThreads) k_flag_flat(const Launch P) {
   __shared__ unsigned long long lds[kThreads / 64];

@@ -149,7 +149,7 @@ struct smfg_workspace {
   int64_t rec_entries;   // capacity of rec: known nodes + samples of a hop
   int64_t hist_entries;  // capacity of hist: row blocks x buckets of a hop
   int split_lg;          // log2 of the most sub-buckets a hop needs (0: no hop splits its buckets)
-  int64_t b_table, b_slot, b_row, b_tiles, b_stiles, b_rec, b_hist, b_bstart, b_bstart2;  // byte sizes of the slab's parts
+  int64_t b_table, b_slot, b_row, b_tiles, b_stiles, b_rec, b_hist, b_bstart, b_bstart2, b_grp;  // byte sizes of the slab's parts
   uint32_t table_log2;
   void* slab;
   uint64_t* table;
@@ -163,6 +163,7 @@ struct smfg_workspace {
   int64_t* rowstart;
   int32_t* rowdeg;
   uint32_t* rank;
+  uint4* grp;
   uint64_t* stile_sums;
   uint64_t* rec;
   uint32_t* hist;
@@ -344,7 +345,8 @@ int plan_workspace(smfg_workspace* ws, const smfg_graph* g, int32_t max_seeds, i
     ws->b_bstart2 = ws->split_lg > 0 ? align256(((int64_t(1) << ws->split_lg) + 2) * 4) : 0;
     ws->bytes = ws->b_slot + 4 * ws->b_row + ws->b_tiles + (ws->split_lg > 0 ? 2 : 1) * ws->b_rec + ws->b_hist +
                 ws->b_bstart + ws->b_bstart2;
-    if (ws->flat) ws->bytes += ws->b_slot + 3 * ws->b_row + ws->b_stiles;
+    ws->b_grp = ws->flat ? align256((ws->slot_entries / 64 + 2) * 16) : 0;
+    if (ws->flat) ws->bytes += ws->b_grp + 3 * ws->b_row + ws->b_stiles;
   } else {
     ws->b_table = align256((int64_t(1) << lg) * 8);
     ws->bytes = ws->b_table + 4 * ws->b_slot + 8 * ws->b_row + ws->b_tiles + ws->b_stiles;
@@ -369,7 +371,7 @@ void bind_workspace(smfg_workspace* ws, void* base) {
       ws->rec2 = reinterpret_cast<uint64_t*>(p); p += ws->b_rec;
     }
     if (ws->flat) {
-      ws->rank = reinterpret_cast<uint32_t*>(p); p += ws->b_slot;
+      ws->grp = reinterpret_cast<uint4*>(p); p += ws->b_grp;
       ws->rowstart = reinterpret_cast<int64_t*>(p); p += 2 * ws->b_row;
       ws->rowdeg = reinterpret_cast<int32_t*>(p); p += ws->b_row;
       ws->stile_sums = reinterpret_cast<uint64_t*>(p);
@@ -666,6 +668,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     B.rowstart = w->rowstart;
     B.rowdeg = w->rowdeg;
     B.rank = w->rank;
+    B.grp = w->grp;
     B.stile_sums = w->stile_sums;
     B.rec = w->rec;
     B.hist = w->hist;
