@@ -404,6 +404,58 @@ __global__ void __launch_bounds__(kThreads) k_split_buckets(const Launch P) {
 // round still overflow (skewed bits), the bucket starts over with one more bit.  With
 // 32 - lgB - lgR <= kPartTableLg bits left every node of a round has a slot of its own (the hash
 // is a bijection), so the retries end.
+// One record into the bucket's table: the slot of its node keeps the smallest value.  False if the
+// table has no slot left.
+__device__ __forceinline__ bool dedup_insert(unsigned long long* tab, unsigned long long rec, uint32_t sl) {
+  const uint32_t node = static_cast<uint32_t>(rec >> 32);
+  // A plain read first: a node sampled thousands of times (a hub) would otherwise queue
+  // thousands of atomics on one LDS word, while most of its records only need to see that
+  // a smaller value is there already.  Slots never lose their node, values only fall.
+  for (uint32_t probes = 0; probes < kPartSlots; ++probes) {
+    unsigned long long old = tab[sl];
+    if (old == kEmpty) old = atomicCAS(&tab[sl], kEmpty, rec);
+    if (old == kEmpty) return true;
+    if (static_cast<uint32_t>(old >> 32) == node) {
+      if (old > rec) atomicMin(&tab[sl], rec);
+      return true;
+    }
+    sl = (sl + 1u) & (kPartSlots - 1u);
+  }
+  return false;
+}
+
+// What the filled table says about one record: a known node must be alone with its id; a sample
+// that is not its node's smallest value learns the node's local id or the position of its first
+// appearance.
+__device__ __forceinline__ void dedup_settle(const Launch& P, const BatchCtx& B, const unsigned long long* tab,
+                                             unsigned long long rec, uint32_t sl) {
+  const uint32_t node = static_cast<uint32_t>(rec >> 32);
+  const uint32_t val = static_cast<uint32_t>(rec);
+  uint32_t least = 0u;
+  uint32_t probes = 0;
+  for (; probes < kPartSlots; ++probes) {
+    const unsigned long long t = tab[sl];
+    if (static_cast<uint32_t>(t >> 32) == node) {
+      least = static_cast<uint32_t>(t);
+      break;
+    }
+    sl = (sl + 1u) & (kPartSlots - 1u);
+  }
+  if (probes == kPartSlots) {  // every inserted node is found again
+    set_status(B, P.L, SMFG_ST_INTERNAL);
+    return;
+  }
+  if (val < kPend) {
+    // a known node: two of them with one id can only be a repeated seed
+    if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
+  } else if (least != val) {
+    // least < kPend: the node's final local id; else least names the position of the first
+    // appearance (least == val: this sample is that first appearance, its entry stays)
+    B.gsrc[val & ~kTagMask] =
+        static_cast<int32_t>(least < kPend ? (kResolved | least) : (kPointer | (least & ~kTagMask)));
+  }
+}
+
 __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
   __shared__ unsigned long long tab[kPartSlots];
   __shared__ int overflow_lds;
@@ -414,6 +466,7 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
   const uint64_t* __restrict__ recs = hs.lg2 == 0 ? B.rec : B.rec2;
   const int free_bits = 32 - hs.lgB - hs.lg2;  // hash bits below the (sub-)bucket's
   const int max_lgR = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
+  constexpr int U = 8;  // records in flight per thread
   for (uint32_t bucket = static_cast<uint32_t>(block_in_batch(P)); bucket < (nB << hs.lg2);
        bucket += static_cast<uint32_t>(blocks_per_batch(P))) {
     // the (sub-)bucket's records
@@ -421,52 +474,44 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
     const uint32_t rec1 = hs.lg2 == 0 ? rec0 + B.bstart[nB + 1 + bucket] : B.bstart2[bucket + 1];
     const uint32_t cnt = rec1 - rec0;
     if (cnt == 0) continue;
+    if (cnt <= kThreads * U && cnt <= kPartSlots / 2) {
+      // the usual bucket: its records stay in registers between the two passes, and a table at most
+      // half full cannot overflow
+      static_assert(kThreads * U <= kPartSlots, "a resident bucket always fits its table");
+      unsigned long long mine[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t r = rec0 + u * kThreads + threadIdx.x;
+        mine[u] = r < rec1 ? recs[r] : kEmpty;
+      }
+      for (uint32_t q = threadIdx.x; q < kPartSlots; q += kThreads) tab[q] = kEmpty;
+      __syncthreads();
+      const int down = free_bits > kPartTableLg ? free_bits - kPartTableLg : 0;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (mine[u] != kEmpty)
+          dedup_insert(tab, mine[u], ((static_cast<uint32_t>(mine[u] >> 32) * kPartHash) >> down) & (kPartSlots - 1u));
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (mine[u] != kEmpty)
+          dedup_settle(P, B, tab, mine[u],
+                       ((static_cast<uint32_t>(mine[u] >> 32) * kPartHash) >> down) & (kPartSlots - 1u));
+      __syncthreads();
+      continue;
+    }
     int lgR = 0;
     while (lgR < max_lgR && (cnt >> lgR) > kPartSlots / 2) ++lgR;
     for (;;) {
       bool failed = false;
       const int rem = free_bits - lgR;  // hash bits below the round's
+      const int down = rem > kPartTableLg ? rem - kPartTableLg : 0;
       const uint32_t rounds = 1u << lgR;
       for (uint32_t round = 0; round < rounds && !failed; ++round) {
         for (uint32_t q = threadIdx.x; q < kPartSlots; q += kThreads) tab[q] = kEmpty;
         if (threadIdx.x == 0) overflow_lds = 0;
         __syncthreads();
-        constexpr int U = 8;  // records in flight per thread
-        for (uint32_t c0 = rec0; c0 < rec1; c0 += kThreads * U) {
-          unsigned long long mine[U];
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const uint32_t r = c0 + u * kThreads + threadIdx.x;
-            mine[u] = r < rec1 ? recs[r] : kEmpty;
-          }
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            if (mine[u] == kEmpty) continue;
-            const uint32_t node = static_cast<uint32_t>(mine[u] >> 32);
-            const uint32_t hsh = node * kPartHash;
-            if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
-            uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
-            // A plain read first: a node sampled thousands of times (a hub) would otherwise queue
-            // thousands of atomics on one LDS word, while most of its records only need to see that
-            // a smaller value is there already.  Slots never lose their node, values only fall.
-            uint32_t probes = 0;
-            for (; probes < kPartSlots; ++probes) {
-              unsigned long long old = tab[sl];
-              if (old == kEmpty) old = atomicCAS(&tab[sl], kEmpty, mine[u]);
-              if (old == kEmpty) break;
-              if (static_cast<uint32_t>(old >> 32) == node) {
-                if (old > mine[u]) atomicMin(&tab[sl], mine[u]);
-                break;
-              }
-              sl = (sl + 1u) & (kPartSlots - 1u);
-            }
-            if (probes == kPartSlots) overflow_lds = 1;
-          }
-        }
-        __syncthreads();
-        failed = overflow_lds != 0;
-        if (!failed) {
-          constexpr int U = 8;
+        for (int pass = 0; pass < 2 && !failed; ++pass) {  // insert, then settle
           for (uint32_t c0 = rec0; c0 < rec1; c0 += kThreads * U) {
             unsigned long long mine[U];
 #pragma unroll
@@ -477,45 +522,26 @@ __global__ void __launch_bounds__(kThreads) k_dedup_buckets(const Launch P) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
               if (mine[u] == kEmpty) continue;
-              const uint32_t node = static_cast<uint32_t>(mine[u] >> 32);
-              const uint32_t val = static_cast<uint32_t>(mine[u]);
-              const uint32_t hsh = node * kPartHash;
+              const uint32_t hsh = static_cast<uint32_t>(mine[u] >> 32) * kPartHash;
               if (lgR != 0 && ((hsh >> rem) & (rounds - 1u)) != round) continue;
-              uint32_t sl = (rem > kPartTableLg ? hsh >> (rem - kPartTableLg) : hsh) & (kPartSlots - 1u);
-              uint32_t least = 0u;
-              uint32_t probes = 0;
-              for (; probes < kPartSlots; ++probes) {
-                const unsigned long long t = tab[sl];
-                if (static_cast<uint32_t>(t >> 32) == node) {
-                  least = static_cast<uint32_t>(t);
-                  break;
-                }
-                sl = (sl + 1u) & (kPartSlots - 1u);
-              }
-              if (probes == kPartSlots) {  // every inserted node is found again
-                set_status(B, P.L, SMFG_ST_INTERNAL);
-                continue;
-              }
-              if (val < kPend) {
-                // a known node: two of them with one id can only be a repeated seed
-                if (least != val) set_status(B, P.L, SMFG_ST_DUPLICATE_SEED);
+              const uint32_t sl = (hsh >> down) & (kPartSlots - 1u);
+              if (pass == 0) {
+                if (!dedup_insert(tab, mine[u], sl)) overflow_lds = 1;
               } else {
-                // least < kPend: the node's final local id; least == val: this sample is the node's
-                // first appearance (entry stays); else least names the position of the first appearance
-                if (least != val)
-                  B.gsrc[val & ~kTagMask] = static_cast<int32_t>(least < kPend ? (kResolved | least)
-                                                                               : (kPointer | (least & ~kTagMask)));
+                dedup_settle(P, B, tab, mine[u], sl);
               }
             }
           }
+          __syncthreads();
+          failed = overflow_lds != 0;
         }
-        __syncthreads();
       }
       if (!failed) break;
       if (lgR >= max_lgR) {  // cannot overflow with a slot per node
         if (threadIdx.x == 0) set_status(B, P.L, SMFG_ST_INTERNAL);
         break;
       }
+      __syncthreads();  // every thread has read the overflow word before the next attempt clears it
       ++lgR;
     }
   }

@@ -76,13 +76,20 @@ __global__ void __launch_bounds__(kThreads) k_scan_count_tiles(const Launch P) {
   }
 }
 
-// A wave takes kWideRows consecutive destinations: lane l first fetches the row record of
-// destination l (start, degree, sample count, block offset: coalesced, once per group of rows),
-// then the wave walks the rows, lane l of round r owning slot s = 64 r + l: first the rows that are
-// one plain round (whole row taken, at most 64 samples; several in flight), then the others one by
-// one.  INSERT: the sample goes into
+// A wave takes up to kWideRows consecutive destinations (fewer when the hop has fewer destinations
+// than that per wave of the grid: a hop of few, long rows then still spreads over the chip): lane l
+// first fetches the row record of destination l (start, degree, sample count, block offset:
+// coalesced, once per group of rows), then the wave walks the rows, lane l of round r owning slot
+// s = 64 r + l: first the rows that are one plain round (whole row taken, at most 64 samples; several
+// in flight), then the others one by one - a row taken whole kWideCopyRounds rounds at a time, a
+// row with drawn positions after Floyd's rule has settled them in the wave's part of the LDS
+// (two arrays of the fanout rounded up to 64 words per wave, sized by the launch; none for
+// SMFG_FANOUT_ALL, where nothing is drawn).  INSERT: the sample goes into
 // the dedup table at once (table strategy); else only its node id is stored (partition strategy).
 constexpr int kWideRows = 16;
+constexpr int kWideCopyRounds = 8;
+constexpr uint32_t wide_lds_words(int d) { return d < 0 ? 0u : (static_cast<uint32_t>(d) + 63u) & ~63u; }
+constexpr size_t wide_lds_bytes(int d) { return sizeof(uint32_t) * 2 * (kThreads / 64) * wide_lds_words(d); }
 
 // What happens to a drawn sample: recorded (partition strategy), or also inserted into the dedup
 // table right away (table strategy; see k_sample_insert for the three cases).
@@ -168,20 +175,21 @@ __device__ __forceinline__ void floyd_positions(const Launch& P, const BatchCtx&
 
 template <bool INSERT>
 __global__ void __launch_bounds__(kThreads) k_sample_wide(const Launch P) {
-  __shared__ uint32_t picks_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
-  __shared__ __align__(16) uint32_t draws_lds[kThreads / 64][SMFG_MAX_WIDE_FANOUT];
+  extern __shared__ __align__(16) uint32_t wide_lds[];
   const BatchCtx& B = P.b[batch_of_block(P)];
   if (__any(status_of(B, P.L) != 0)) return;  // whole waves only: the lanes below cooperate
   const int n = static_cast<int>(B.counts[P.h]);
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  uint32_t* picks = picks_lds[wave];
-  uint32_t* draws = draws_lds[wave];
+  uint32_t* draws = wide_lds + 2 * wave * wide_lds_words(P.d);
+  uint32_t* picks = draws + wide_lds_words(P.d);
   const int waves_total = blocks_per_batch(P) * (kThreads / 64);
-  for (int i0 = (block_in_batch(P) * (kThreads / 64) + wave) * kWideRows; i0 < n; i0 += waves_total * kWideRows) {
+  int per = (n + waves_total - 1) / waves_total;  // destinations per wave and turn
+  per = per < 1 ? 1 : (per > kWideRows ? kWideRows : per);
+  for (int i0 = (block_in_batch(P) * (kThreads / 64) + wave) * per; i0 < n; i0 += waves_total * per) {
     const int il = i0 + lane;
     uint32_t v_l = 0, deg_l = 0, k_l = 0, base_l = 0, a_lo = 0, a_hi = 0;
-    if (lane < kWideRows && il < n) {
+    if (lane < per && il < n) {
       v_l = static_cast<uint32_t>(B.node_ids[il]);
       const int64_t a = B.rowstart[il];
       a_lo = static_cast<uint32_t>(a);
@@ -191,8 +199,8 @@ __global__ void __launch_bounds__(kThreads) k_sample_wide(const Launch P) {
       base_l = static_cast<uint32_t>(B.tile_sums[il / kTileRows]) + static_cast<uint32_t>(B.rowoff[il]);
       B.blk_indptr[il] = static_cast<int32_t>(base_l);
     }
-    const int rows = n - i0 < kWideRows ? n - i0 : kWideRows;
-    static_assert(kWideRows % 4 == 0, "rows are walked four at a time");
+    const int rows = n - i0 < per ? n - i0 : per;
+    static_assert(kWideRows % 4 == 0 && kWideRows <= 64, "rows are walked four at a time, a lane per row record");
     for (int r0 = 0; r0 < rows; r0 += 4) {  // lanes beyond the last row hold k = 0
       uint32_t g[4], pos[4];
       bool on[4];
@@ -218,19 +226,34 @@ __global__ void __launch_bounds__(kThreads) k_sample_wide(const Launch P) {
       const uint32_t base = __shfl(base_l, r, 64);
       const bool floyd = deg > k;  // only then are positions drawn (k = fanout <= SMFG_MAX_WIDE_FANOUT)
       if (!floyd && k <= 64u) continue;  // done above
-      if (floyd) floyd_positions(P, B, v, deg, k, picks, draws);
-      for (uint32_t s0 = 0; s0 < k; s0 += 128) {  // two rounds at a time: both reads leave before either result is used
+      if (!floyd) {  // the whole row in CSR order; every read of a turn leaves before a result is used
+        for (uint32_t s0 = static_cast<uint32_t>(lane); s0 < k; s0 += 64u * kWideCopyRounds) {
+          uint32_t gv[kWideCopyRounds];
+#pragma unroll
+          for (int u = 0; u < kWideCopyRounds; ++u) {
+            const uint32_t sl = s0 + 64u * u;
+            gv[u] = sl < k ? static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + sl))) : 0u;
+          }
+#pragma unroll
+          for (int u = 0; u < kWideCopyRounds; ++u) {
+            const uint32_t sl = s0 + 64u * u;
+            if (sl < k) wide_emit<INSERT>(P, B, gv[u], base + sl);
+          }
+        }
+        continue;
+      }
+      floyd_positions(P, B, v, deg, k, picks, draws);
+      for (uint32_t s0 = 0; s0 < k; s0 += 128) {  // two rounds at a time
         const uint32_t sa = s0 + static_cast<uint32_t>(lane), sb = sa + 64u;
         uint32_t ga = 0, gb = 0;
-        if (sa < k) ga = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + (floyd ? picks[sa] : sa))));
-        if (sb < k) gb = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + (floyd ? picks[sb] : sb))));
-        if (sa < k) wide_emit<INSERT>(P, B, ga, base + sa);  // whole row in CSR order when nothing is drawn
+        if (sa < k) ga = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + picks[sa])));
+        if (sb < k) gb = static_cast<uint32_t>(__builtin_nontemporal_load(P.indices + (a + picks[sb])));
+        if (sa < k) wide_emit<INSERT>(P, B, ga, base + sa);
         if (sb < k) wide_emit<INSERT>(P, B, gb, base + sb);
       }
-      if (floyd) {  // the next row's draws must not overwrite picks a lane has yet to read
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
+      // the next row's draws must not overwrite picks a lane has yet to read
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }

@@ -800,7 +800,8 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       int64_t samples = P.d < 0 ? max_entries : rows * P.d;  // upper bound of E_h
       if (samples > max_entries) samples = max_entries;
       const unsigned flat_blocks = blocks_for(samples, kWideTile, kCap);
-      const unsigned wave_blocks = blocks_for(rows, kWideRows * (kThreads / 64), 2 * kCap);
+      // a wave per destination while the grid allows; beyond that a wave takes several (see k_sample_wide)
+      const unsigned wave_blocks = blocks_for(rows, kThreads / 64, 2 * kCap);
       {
         StageTimer t_(SMFG_STAGE_SCAN_TILES, st);
         k_count_rows<<<tile_blocks * G, kThreads, 0, st>>>(P);
@@ -815,7 +816,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
         const unsigned buckets = 1u << P.lgB;
         {
           StageTimer t_(SMFG_STAGE_SAMPLE, st);
-          k_sample_wide<false><<<wave_blocks * G, kThreads, 0, st>>>(P);
+          k_sample_wide<false><<<wave_blocks * G, kThreads, wide_lds_bytes(P.d), st>>>(P);
         }
         {
           StageTimer t_(SMFG_STAGE_PARTITION, st);
@@ -844,7 +845,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       }
       {
         StageTimer t_(SMFG_STAGE_SAMPLE, st);
-        k_sample_wide<true><<<wave_blocks * G, kThreads, 0, st>>>(P);
+        k_sample_wide<true><<<wave_blocks * G, kThreads, wide_lds_bytes(P.d), st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_FLAG, st);
