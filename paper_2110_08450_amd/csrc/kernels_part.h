@@ -53,14 +53,27 @@ constexpr int kFlatBlock = 8192;  // stream elements (known nodes, then samples)
 struct HopShape {
   int lgB, lg2;
 };
+// 2^lg buckets in all: one level up to 2^kPartMaxLgB of them; beyond that two levels, the first of
+// only 2^kPartSplitLgB buckets (more if the second would exceed 2^kPartMaxLg2), so that what a
+// block sends to a bucket per round is a run of a sector or more and the lines it is filling stay
+// in the L2 until they are full.
+constexpr int kPartSplitLgB = 7;
+__host__ __device__ inline void part_levels(int lg, int& lgB, int& lg2) {
+  if (lg <= kPartMaxLgB) {
+    lgB = lg;
+    lg2 = 0;
+    return;
+  }
+  lgB = lg - kPartMaxLg2 > kPartSplitLgB ? lg - kPartMaxLg2 : kPartSplitLgB;
+  lg2 = lg - lgB;
+}
 __device__ __forceinline__ HopShape hop_shape(const Launch& P, const BatchCtx& B) {
   HopShape s{P.lgB, P.lg2};
   if (P.flat) {
     const long long records = B.counts[P.h] + B.counts[P.L + 1 + P.h];
     int lg = 0;
     while (lg < P.lgB + P.lg2 && (records >> lg) > kPartBucketRecords) ++lg;
-    s.lgB = lg < P.lgB ? lg : P.lgB;
-    s.lg2 = lg - s.lgB;
+    part_levels(lg, s.lgB, s.lg2);
   }
   return s;
 }

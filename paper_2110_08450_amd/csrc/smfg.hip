@@ -222,8 +222,7 @@ HopPlan plan_hop(int64_t max_rows, int d) {
   const int64_t records = max_rows * (1 + d);
   int lg = 0;
   while (lg < kPartMaxLgB + kPartMaxLg2 && (records >> lg) > kPartBucketRecords) ++lg;
-  hp.lgB = lg < kPartMaxLgB ? lg : kPartMaxLgB;
-  hp.lg2 = lg - hp.lgB;
+  part_levels(lg, hp.lgB, hp.lg2);
   int64_t cap = (max_rows + 511) / 512;
   cap = cap < 512 ? 512 : (cap > 4096 ? 4096 : cap);
   hp.block_rows = (64 / d) * (kThreads / 64);
@@ -280,7 +279,9 @@ bool part_needs(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t nu
     if (records > kPartMaxRecords) return false;
     const HopPlan hp = plan_hop(rows[h], fanouts[h]);
     if (records > *rec_entries) *rec_entries = records;
-    if ((hp.row_blocks << hp.lgB) > *hist_entries) *hist_entries = hp.row_blocks << hp.lgB;
+    // a call with fewer seeds may take one level of up to 2^kPartMaxLgB buckets where this bound takes two
+    const int lg1 = hp.lgB + hp.lg2 < kPartMaxLgB ? hp.lgB + hp.lg2 : kPartMaxLgB;
+    if ((hp.row_blocks << lg1) > *hist_entries) *hist_entries = hp.row_blocks << lg1;
     if (hp.lg2 > 0 && hp.lgB + hp.lg2 > *split_lg) *split_lg = hp.lgB + hp.lg2;
   }
   if (*rec_entries < kPartMinRecords && !part_forced()) return false;
