@@ -8,9 +8,10 @@
 //                 (value = tag | scan position);
 //   scan_hist     turns the counts of a bucket over the row blocks into offsets, bucket sizes;
 //   scatter       moves the records into their buckets (one contiguous range of `rec` each);
-//   split_buckets only for hops with more records than 1024 buckets of the target size hold: one
-//                 block per bucket orders the bucket's records by further hash bits into
-//                 sub-buckets (`rec2`), which then take the place of the buckets;
+//   split_buckets only for hops with more records than 1024 buckets of the target size hold (such
+//                 a hop starts with fewer, larger buckets, see part_levels): one block per bucket
+//                 orders the bucket's records by further hash bits into sub-buckets (`rec2`),
+//                 which then take the place of the buckets;
 //   dedup_buckets one block per bucket builds a hash table of the bucket's nodes in LDS, keeping
 //                 the smallest value per node (a known node's local id always wins, else the
 //                 earliest scan position).  A sample that is its node's first appearance keeps
@@ -30,7 +31,7 @@
 
 namespace smfg_dev {
 
-constexpr int kPartMaxLgB = 10;                     // at most 1024 buckets per hop ...
+constexpr int kPartMaxLgB = 10;                     // at most 1024 buckets per hop and level ...
 constexpr int kPartMaxLg2 = 10;                     // ... each split into at most 1024 sub-buckets
 constexpr int kPartTableLg = 12;                    // LDS table: 4096 slots of 8 bytes
 constexpr uint32_t kPartSlots = 1u << kPartTableLg;

@@ -206,9 +206,9 @@ int check_fanouts(int32_t L, const int32_t* fanouts, bool* wide = nullptr) {
 
 inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 
-// Launch shape of one hop under the partition strategy: 2^lgB hash buckets (at most 1024), each
-// split once more into 2^lg2 sub-buckets if the records would otherwise exceed kPartBucketRecords
-// per bucket on average in the worst case; destinations cut into row blocks that are whole
+// Launch shape of one hop under the partition strategy: 2^lgB hash buckets (at most 1024) sized for
+// kPartBucketRecords records on average in the worst case; a hop that needs more buckets than that
+// takes two levels, 2^lgB buckets each split into 2^lg2 (part_levels); destinations cut into row blocks that are whole
 // multiples of what a thread block draws at once, at most 512 of them (more for hops beyond
 // 256 K destinations, up to 4096).
 struct HopPlan {

@@ -627,7 +627,7 @@ def test_giant_hub_and_isolated_seeds():
 
 def test_partition_bucket_overflow_and_rounds(dedup_strategy):
     """The partition strategy's per-bucket LDS table: 5000 distinct nodes whose hashes share their
-    12 leading bits all land in one of 1024 buckets and, on the first attempt, in one round of that
+    12 leading bits all land in one bucket and, on the first attempt, in one round of that
     bucket, which overflows the 4096-slot table; the bucket must start over with more rounds and
     still number every node exactly as the serial walk does.  Each of those nodes is sampled 12
     times (60 000 single-neighbour destinations), so the rounds also see repeats."""
