@@ -36,15 +36,19 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 
 
 def source_hash():
-    """sha256 over the library's sources (kernels, host side, header): names the code a stored
-    counter figure was measured on."""
+    """sha256 over the library's sources (kernels, host side, header) without their comments and
+    blank space: names the code a stored counter figure was measured on."""
     import hashlib
+    import re
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2110_08450_amd", "csrc")
     files = sorted(os.path.join(csrc, f) for f in os.listdir(csrc)) + [os.path.join(ROOT, "include", "smfg.h")]
     for f in files:
+        text = open(f, "r", encoding="utf-8").read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)   # no string literal of these files holds a comment mark
+        text = re.sub(r"//[^\n]*", " ", text)
         h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 

@@ -1,6 +1,6 @@
 // libsmfg wide path: fanouts above SMFG_MAX_FANOUT and SMFG_FANOUT_ALL, samples at exact block offsets.
-// count_rows / scan_count_tiles fix the offsets; then either the table strategy (sample_insert_wide,
-// flag_flat, scan_flat_tiles, assemble_flat) or the partition strategy (sample_wide, hist_flat,
+// count_rows / scan_count_tiles fix the offsets; then either the table strategy (sample_wide<true>,
+// flag_flat, scan_flat_tiles, assemble_flat) or the partition strategy (sample_wide<false>, hist_flat,
 // scan_hist, scatter_flat, [split_buckets], dedup_buckets, flag_flat_part, scan_flat_tiles,
 // assemble_flat_part) turns the samples into local ids.
 #ifndef SMFG_KERNELS_WIDE_H_
