@@ -145,7 +145,7 @@ struct smfg_workspace {
   int64_t bytes;
   // partition strategy (no dedup table) or table strategy; fixed when the workspace is planned
   bool part;
-  bool flat;             // partition strategy also over exact offsets (wide fanouts): rank, row starts etc. present
+  bool flat;             // partition strategy also over exact offsets (wide fanouts): group records, row starts etc. present
   int64_t rec_entries;   // capacity of rec: known nodes + samples of a hop
   int64_t hist_entries;  // capacity of hist: row blocks x buckets of a hop
   int split_lg;          // log2 of the most sub-buckets a hop needs (0: no hop splits its buckets)
