@@ -2,6 +2,7 @@
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -123,3 +124,34 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bucket_levels_of_the_partition_strategy(tmp_path):
+    """Host logic shared with the kernels: how 2^lg hash buckets are laid out in one or two levels.
+    Both levels stay within what the kernels' LDS arrays hold, together they give exactly 2^lg
+    buckets, and a hop takes two levels only when one cannot hold it."""
+    import shutil
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("no hipcc")
+    csrc = os.path.join(ROOT, "paper_2110_08450_amd", "csrc")
+    src = tmp_path / "levels.hip"
+    src.write_text('#include <cstdio>\n#include "kernels_part.h"\n'
+                   'int main() {\n'
+                   '  std::printf("%d %d %d\\n", smfg_dev::kPartMaxLgB, smfg_dev::kPartMaxLg2, smfg_dev::kPartSplitLgB);\n'
+                   '  for (int lg = 0; lg <= smfg_dev::kPartMaxLgB + smfg_dev::kPartMaxLg2; ++lg) {\n'
+                   '    int a = -1, b = -1;\n    smfg_dev::part_levels(lg, a, b);\n    std::printf("%d %d %d\\n", lg, a, b);\n  }\n'
+                   '  return 0;\n}\n')
+    exe = tmp_path / "levels"
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-O1", "-I", csrc, "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True, capture_output=True, timeout=300)
+    lines = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=60).stdout.split("\n")
+    max_b, max_2, split_b = map(int, lines[0].split())
+    rows = [tuple(map(int, l.split())) for l in lines[1:] if l.strip()]
+    assert [r[0] for r in rows] == list(range(max_b + max_2 + 1))
+    for lg, lg_b, lg_2 in rows:
+        assert lg_b + lg_2 == lg and 0 <= lg_b <= max_b and 0 <= lg_2 <= max_2
+        if lg <= max_b:
+            assert lg_2 == 0
+        else:
+            assert lg_b >= min(split_b, max_b) and lg_2 > 0
