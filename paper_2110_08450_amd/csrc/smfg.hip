@@ -204,6 +204,16 @@ int check_fanouts(int32_t L, const int32_t* fanouts, bool* wide = nullptr) {
   return SMFG_OK;
 }
 
+// Blocks per batch of k_dedup_buckets.  A hop of one level: a block per bucket.  A hop of two
+// levels has thousands of sub-buckets per batch: about 4096 blocks over the whole launch, each
+// taking several sub-buckets one after the other - the scattered writes a sub-bucket leaves behind
+// then drain while the block is busy with its next one, instead of holding the block's LDS until
+// they are done.
+inline unsigned dedup_blocks(int lgB, int lg2, unsigned batches) {
+  if (lg2 == 0) return 1u << lgB;
+  const unsigned cap = 4096u / batches > 512u ? 4096u / batches : 512u;
+  return blocks_for(int64_t(1) << (lgB + lg2), 1, cap);
+}
 inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 
 // Launch shape of one hop under the partition strategy: 2^lgB hash buckets (at most 1024) sized for
@@ -781,7 +791,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
       }
       {
         StageTimer t_(SMFG_STAGE_DEDUP, st);
-        k_dedup_buckets<<<blocks_for(int64_t(buckets) << P.lg2, 1, 2 * kCap) * G, kThreads, 0, st>>>(P);
+        k_dedup_buckets<<<dedup_blocks(P.lgB, P.lg2, G) * G, kThreads, 0, st>>>(P);
       }
       {
         StageTimer t_(SMFG_STAGE_FLAG, st);
@@ -828,7 +838,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
         }
         {
           StageTimer t_(SMFG_STAGE_DEDUP, st);
-          k_dedup_buckets<<<blocks_for(int64_t(buckets) << P.lg2, 1, 2 * kCap) * G, kThreads, 0, st>>>(P);
+          k_dedup_buckets<<<dedup_blocks(P.lgB, P.lg2, G) * G, kThreads, 0, st>>>(P);
         }
         {
           StageTimer t_(SMFG_STAGE_FLAG, st);
