@@ -219,22 +219,23 @@ inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 // Launch shape of one hop under the partition strategy: 2^lgB hash buckets (at most 1024) sized for
 // kPartBucketRecords records on average in the worst case; a hop that needs more buckets than that
 // takes two levels, 2^lgB buckets each split into 2^lg2 (part_levels); destinations cut into row blocks that are whole
-// multiples of what a thread block draws at once, at most 512 of them (more for hops beyond
-// 256 K destinations, up to 4096).
+// multiples of what a thread block draws at once, at most 512 of them (256 in a launch of more than
+// 8 batches; more for hops beyond 256 K destinations, up to 4096).
 struct HopPlan {
   int lgB, lg2;
   int block_rows;
   int64_t row_blocks;
 };
 
-HopPlan plan_hop(int64_t max_rows, int d) {
+HopPlan plan_hop(int64_t max_rows, int d, int batches) {
   HopPlan hp;
   const int64_t records = max_rows * (1 + d);
   int lg = 0;
   while (lg < kPartMaxLgB + kPartMaxLg2 && (records >> lg) > kPartBucketRecords) ++lg;
   part_levels(lg, hp.lgB, hp.lg2);
   int64_t cap = (max_rows + 511) / 512;
-  cap = cap < 512 ? 512 : (cap > 4096 ? 4096 : cap);
+  const int64_t least = batches > 8 ? 256 : 512;  // about 4096 row blocks over a launch of many batches
+  cap = cap < least ? least : (cap > 4096 ? 4096 : cap);
   hp.block_rows = (64 / d) * (kThreads / 64);
   while ((max_rows + hp.block_rows - 1) / hp.block_rows > cap) hp.block_rows *= 2;
   hp.row_blocks = (max_rows + hp.block_rows - 1) / hp.block_rows;
@@ -287,7 +288,7 @@ bool part_needs(int32_t num_seeds, int32_t L, const int32_t* fanouts, int64_t nu
   for (int h = 0; h < L; ++h) {
     const int64_t records = rows[h] * (1 + fanouts[h]);
     if (records > kPartMaxRecords) return false;
-    const HopPlan hp = plan_hop(rows[h], fanouts[h]);
+    const HopPlan hp = plan_hop(rows[h], fanouts[h], 1);  // the most row blocks any launch will use
     if (records > *rec_entries) *rec_entries = records;
     // a call with fewer seeds may take one level of up to 2^kPartMaxLgB buckets where this bound takes two
     const int lg1 = hp.lgB + hp.lg2 < kPartMaxLgB ? hp.lgB + hp.lg2 : kPartMaxLgB;
@@ -738,7 +739,7 @@ int smfg_sample_mfg_many(const smfg_graph_t* g, smfg_workspace_t* const* ws, con
     flat_plan.row_blocks = (bound + kFlatBlock - 1) / kFlatBlock;
   } else if (part) {
     for (int h = 0; h < L; ++h) {
-      plan[h] = plan_hop(max_n[h], fanouts[h]);
+      plan[h] = plan_hop(max_n[h], fanouts[h], num_batches);
       const int64_t records = max_n[h] * (1 + fanouts[h]);
       for (int b = 0; b < num_batches; ++b)
         if (records > ws[b]->rec_entries || (plan[h].row_blocks << plan[h].lgB) > ws[b]->hist_entries ||
