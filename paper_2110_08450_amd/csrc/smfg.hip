@@ -219,7 +219,7 @@ inline int64_t align256(int64_t x) { return (x + 255) & ~int64_t(255); }
 // Launch shape of one hop under the partition strategy: 2^lgB hash buckets (at most 1024) sized for
 // kPartBucketRecords records on average in the worst case; a hop that needs more buckets than that
 // takes two levels, 2^lgB buckets each split into 2^lg2 (part_levels); destinations cut into row blocks that are whole
-// multiples of what a thread block draws at once, at most 512 of them (256 in a launch of more than
+// multiples of what a thread block draws at once, at most 512 of them (128 in a launch of more than
 // 8 batches; more for hops beyond 256 K destinations, up to 4096).
 struct HopPlan {
   int lgB, lg2;
@@ -234,7 +234,7 @@ HopPlan plan_hop(int64_t max_rows, int d, int batches) {
   while (lg < kPartMaxLgB + kPartMaxLg2 && (records >> lg) > kPartBucketRecords) ++lg;
   part_levels(lg, hp.lgB, hp.lg2);
   int64_t cap = (max_rows + 511) / 512;
-  const int64_t least = batches > 8 ? 256 : 512;  // about 4096 row blocks over a launch of many batches
+  const int64_t least = batches > 8 ? 128 : 512;  // fewer, longer row blocks when many batches fill the chip anyway
   cap = cap < least ? least : (cap > 4096 ? 4096 : cap);
   hp.block_rows = (64 / d) * (kThreads / 64);
   while ((max_rows + hp.block_rows - 1) / hp.block_rows > cap) hp.block_rows *= 2;
