@@ -128,8 +128,9 @@ int smfg_bounds(int32_t num_seeds, int32_t L, const int32_t *fanouts, int64_t nu
                 int64_t *max_nodes, int64_t *max_edges);
 
 /*
- * Scratch for one batch in flight: dedup table (>= 2 slots per node of capacity), per-sample
- * slot memory, per-row counters, scan partials.  Sized for up to max_seeds seeds, the given
+ * Scratch for one batch in flight: per-sample and per-row state, scan partials and, by dedup
+ * strategy (smfg_workspace_strategy), the records of a hop with their bucket counts and offsets,
+ * or a dedup table (>= 2 slots per node of capacity).  Sized for up to max_seeds seeds, the given
  * fanouts (a later call may use the same or smaller fanouts / fewer hops) and node_capacity
  * distinct nodes (0 = the worst case of smfg_bounds).  Allocates device memory with hipMalloc,
  * zeroes part of it and synchronises the device once; not for use inside a stream capture.
