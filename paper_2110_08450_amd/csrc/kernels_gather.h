@@ -13,34 +13,68 @@ namespace smfg_dev {
 // A row id outside [0, num_nodes) is read as row 0, so that no id can cause a read outside x.
 constexpr int kGatherRows = 32;
 
-// The copy's loads and stores carry cache-policy bits that the compiler's non-temporal builtins
-// do not set (those give `nt` alone), so the 16-, 8- and 4-byte accesses are written out.  Rows are
-// read once and written once: `nt` keeps them from displacing what the sampling kernels beside
-// the copy have in the caches (without it the whole path loses 8-13 %); on top of that, stores
-// with `sc0` measured +2.5 to +3 % on the papers100M-, arxiv- and products-shaped workloads, and
-// loads at system scope (`sc0 sc1`) for the 16-byte rows another +1.4 % on the first (means of
-// six interleaved runs).  Which level a line is kept in does not change what is copied: the
-// table is read-only, and the kernel's end makes every store visible to what follows.
+// The copy's loads and stores are written out as instructions, for two reasons.  Cache policy:
+// rows are read once and written once, and the compiler's non-temporal builtins set `nt` alone.
+// `nt` keeps the rows from displacing what the sampling kernels beside the copy have in the
+// caches (without it the whole path loses 8-13 %); stores with `sc0` on top measured +2.5 to +3 %
+// on the papers100M-, arxiv- and products-shaped workloads, loads at system scope (`sc0 sc1`)
+// another +1.4 % on the first (means of six interleaved runs).  Issue order: the two loads of a
+// round leave together and its two stores leave back to back after one wait; the compiler put a
+// wait between the stores, which cost the 200-byte rows of the products-shaped workload 3 %.
+// Which level a line is kept in does not change what is copied: the table is read-only, and the
+// kernel's end makes every store visible to what follows.  The wait is part of the load
+// statements because the compiler does not track loads it did not emit; for the same reason a
+// store is followed by two idle cycles: the hardware reads a wide store's data registers a
+// moment after issue and wants no vector write to them in between, a gap the compiler only
+// inserts after stores of its own.
 template <typename V>
 __device__ __forceinline__ void store_streaming(V v, V* p) {
   if constexpr (sizeof(V) == 16) {
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 nt" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
   } else if constexpr (sizeof(V) == 8) {
-    asm volatile("global_store_dwordx2 %0, %1, off sc0 nt" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
   } else if constexpr (sizeof(V) == 4) {
-    asm volatile("global_store_dword %0, %1, off sc0 nt" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dword %0, %1, off sc0 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
   } else {
     __builtin_nontemporal_store(v, p);
   }
 }
-// Two loads issued together; both have arrived when this returns (the wait is part of the
-// statement, because the compiler does not track loads it did not emit).
+template <typename V>
+__device__ __forceinline__ V load_streaming(const V* p) {
+  V v;
+  if constexpr (sizeof(V) == 16) {
+    asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p) : "memory");
+  } else if constexpr (sizeof(V) == 8) {
+    asm volatile("global_load_dwordx2 %0, %1, off sc0 sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p) : "memory");
+  } else if constexpr (sizeof(V) == 4) {
+    asm volatile("global_load_dword %0, %1, off sc0 sc1 nt\n\ts_waitcnt vmcnt(0)" : "=&v"(v) : "v"(p) : "memory");
+  } else {
+    v = __builtin_nontemporal_load(p);
+  }
+  return v;
+}
 template <typename V>
 __device__ __forceinline__ void load_pair_streaming(const V* p0, const V* p1, V& v0, V& v1) {
   if constexpr (sizeof(V) == 16) {
     asm volatile(
         "global_load_dwordx4 %0, %2, off sc0 sc1 nt\n\t"
         "global_load_dwordx4 %1, %3, off sc0 sc1 nt\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(v0), "=&v"(v1)
+        : "v"(p0), "v"(p1)
+        : "memory");
+  } else if constexpr (sizeof(V) == 8) {
+    asm volatile(
+        "global_load_dwordx2 %0, %2, off sc0 sc1 nt\n\t"
+        "global_load_dwordx2 %1, %3, off sc0 sc1 nt\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(v0), "=&v"(v1)
+        : "v"(p0), "v"(p1)
+        : "memory");
+  } else if constexpr (sizeof(V) == 4) {
+    asm volatile(
+        "global_load_dword %0, %2, off sc0 sc1 nt\n\t"
+        "global_load_dword %1, %3, off sc0 sc1 nt\n\t"
         "s_waitcnt vmcnt(0)"
         : "=&v"(v0), "=&v"(v1)
         : "v"(p0), "v"(p1)
@@ -56,7 +90,6 @@ __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, in
                                             uint32_t vec_per_row, int64_t num_nodes,
                                             const int32_t* __restrict__ ids, int64_t n,
                                             uint8_t* __restrict__ out) {
-  constexpr int U = 2;
   __shared__ int64_t row_byte[kGatherRows];  // byte offset of each source row
   const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kGatherRows;
   if (r0 >= n) return;
@@ -74,28 +107,21 @@ __device__ __forceinline__ void gather_rows(const uint8_t* __restrict__ feat, in
   // when a row has at most 8192 vectors; longer rows divide
   const bool by_mul = vec_per_row <= 8192u;
   const uint64_t inv = 0xFFFFFFFFull / vec_per_row + 1ull;
-  uint32_t base = threadIdx.x;
-  // full rounds: U independent row reads in flight per thread, then the U stores
-  for (; base + (U - 1) * kThreads < cnt; base += kThreads * U) {
-    static_assert(U == 2, "the loads of a round are issued as one pair");
-    V val[U];
-    const V* src[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint32_t idx = base + u * kThreads;
-      const uint32_t jrow = by_mul ? static_cast<uint32_t>((idx * inv) >> 32) : idx / vec_per_row;
-      const uint32_t c = idx - jrow * vec_per_row;
-      src[u] = reinterpret_cast<const V*>(feat + row_byte[jrow]) + c;
+  const auto source = [&](uint32_t idx) {
+    const uint32_t jrow = by_mul ? static_cast<uint32_t>((idx * inv) >> 32) : idx / vec_per_row;
+    return reinterpret_cast<const V*>(feat + row_byte[jrow]) + (idx - jrow * vec_per_row);
+  };
+  // a round: two independent row reads per thread, then the two stores; the last round of a
+  // thread may hold one vector only
+  for (uint32_t base = threadIdx.x; base < cnt; base += kThreads * 2) {
+    if (base + kThreads < cnt) {
+      V v0, v1;
+      load_pair_streaming(source(base), source(base + kThreads), v0, v1);
+      store_streaming(v0, o + base);
+      store_streaming(v1, o + base + kThreads);
+    } else {
+      store_streaming(load_streaming(source(base)), o + base);
     }
-    load_pair_streaming(src[0], src[1], val[0], val[1]);
-#pragma unroll
-    for (int u = 0; u < U; ++u) store_streaming(val[u], o + base + u * kThreads);
-  }
-  for (; base < cnt; base += kThreads) {
-    const uint32_t jrow = by_mul ? static_cast<uint32_t>((base * inv) >> 32) : base / vec_per_row;
-    const uint32_t c = base - jrow * vec_per_row;
-    __builtin_nontemporal_store(
-        __builtin_nontemporal_load(reinterpret_cast<const V*>(feat + row_byte[jrow]) + c), o + base);
   }
 }
 
