@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 # Launch configuration per workload: (batches per launch set, sampling streams, buffer sets).
 # Small batches are bound by the latency of the chain of short kernels, so they take more batches
 # per set and two sampling streams; the largest batches fill the chip one at a time.
-LAUNCH_CONFIG = {"tiny": (4, 1, 2), "mid": (16, 2, 3), "large": (8, 1, 2), "papers": (8, 1, 2),
+LAUNCH_CONFIG = {"tiny": (4, 1, 2), "mid": (16, 2, 3), "large": (8, 2, 3), "papers": (8, 1, 2),
                  "papers_infer": (1, 2, 3), "large_wide": (4, 2, 3), "large_all": (4, 2, 3)}
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 
