@@ -421,16 +421,33 @@ int static_scratch_of(int device, void** out) {
 }
 
 // The gather launch shared by smfg_sample_mfg_many and smfg_gather_many.
-void launch_gather(const Launch& P, int64_t max_rows, int vb, unsigned G, hipStream_t st) {
-  const unsigned gb = blocks_for(max_rows, kGatherRows, 0x7FFFFFFFu);
-  StageTimer t_(SMFG_STAGE_GATHER, st);
+template <int ROWS>
+void launch_gather_rows(const Launch& P, int64_t max_rows, int vb, unsigned G, hipStream_t st) {
+  const unsigned gb = blocks_for(max_rows, ROWS, 0x7FFFFFFFu);
   switch (vb) {
-    case 16: k_gather<u32x4><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-    case 8: k_gather<u32x2><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-    case 4: k_gather<uint32_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-    case 2: k_gather<uint16_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
-    default: k_gather<uint8_t><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    case 16: k_gather<u32x4, ROWS><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    case 8: k_gather<u32x2, ROWS><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    case 4: k_gather<uint32_t, ROWS><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    case 2: k_gather<uint16_t, ROWS><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
+    default: k_gather<uint8_t, ROWS><<<dim3(gb, G), kThreads, 0, st>>>(P); break;
   }
+}
+template <int ROWS>
+void launch_gather_plain(const smfg_graph* g, int vb, const int32_t* d_node_ids, const int64_t* d_num_rows,
+                         int64_t max_rows, uint8_t* o, hipStream_t st) {
+  const unsigned gb = blocks_for(max_rows, ROWS, 0x7FFFFFFFu);
+  switch (vb) {
+    case 16: k_gather_plain<u32x4, ROWS><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    case 8: k_gather_plain<u32x2, ROWS><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    case 4: k_gather_plain<uint32_t, ROWS><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    case 2: k_gather_plain<uint16_t, ROWS><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+    default: k_gather_plain<uint8_t, ROWS><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
+  }
+}
+void launch_gather(const Launch& P, int64_t max_rows, int vb, unsigned G, hipStream_t st) {
+  StageTimer t_(SMFG_STAGE_GATHER, st);
+  if (gather_rows_per_block(P.row_bytes) == 64) launch_gather_rows<64>(P, max_rows, vb, G, st);
+  else launch_gather_rows<32>(P, max_rows, vb, G, st);
 }
 
 }  // namespace
@@ -985,18 +1002,12 @@ int smfg_gather_rows(const smfg_graph_t* g, const int32_t* d_node_ids, const int
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int vb = vec_bytes(reinterpret_cast<uintptr_t>(g->feat), reinterpret_cast<uintptr_t>(d_out), g->row_bytes,
                            g->row_stride);
-  const unsigned gb = blocks_for(max_rows, kGatherRows, 0x7FFFFFFFu);
   uint8_t* o = static_cast<uint8_t*>(d_out);
   int cur = 0;
   (void)hipGetDevice(&cur);
   if (cur != g->device) (void)hipSetDevice(g->device);
-  switch (vb) {
-    case 16: k_gather_plain<u32x4><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
-    case 8: k_gather_plain<u32x2><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
-    case 4: k_gather_plain<uint32_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
-    case 2: k_gather_plain<uint16_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
-    default: k_gather_plain<uint8_t><<<gb, kThreads, 0, st>>>(g->feat, g->row_bytes, g->row_stride, g->num_nodes, d_node_ids, d_num_rows, max_rows, o); break;
-  }
+  if (gather_rows_per_block(g->row_bytes) == 64) launch_gather_plain<64>(g, vb, d_node_ids, d_num_rows, max_rows, o, st);
+  else launch_gather_plain<32>(g, vb, d_node_ids, d_num_rows, max_rows, o, st);
   hipError_t e = hipGetLastError();
   if (cur != g->device) (void)hipSetDevice(cur);
   return hip_err(e);
