@@ -94,14 +94,16 @@ def traffic_from(fetch_csv, write_csv, bench_json):
                 acc.setdefault(m.group(1), []).append((float(r["Counter_Value"]), int(r["Grid_Size"])))
         return acc
     fe, wr = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
-    # the identity gather: grid = ceil(rows / 32) blocks of 256 threads, rows x row_bytes in and out (+ 4 B ids in)
+    # the identity gather: grid = ceil(rows / rows per block) blocks of 256 threads (the library copies 64 rows
+    # per block when a row has fewer than 256 bytes, else 32), rows x row_bytes in and out (+ 4 B ids in)
     import torch  # noqa: F401  (only for the workload table's dtypes)
     from paper_2110_08450_amd import synth
     w = synth.WORKLOADS[workload]
     row_bytes = w.feat_dim * (2 if "16" in str(w.feat_dtype) else 4)
     (f_plain, grid), (w_plain, _) = fe["k_gather_plain"][0], wr["k_gather_plain"][0]
     rows = min((1 << 30) // row_bytes, w.num_nodes)
-    assert (rows + 31) // 32 * 256 == grid, "the calibration launch is not the identity gather this expects"
+    per_block = 64 if row_bytes < 256 else 32
+    assert (rows + per_block - 1) // per_block * 256 == grid, "the calibration launch is not the identity gather this expects"
     fetch_scale = (rows * (row_bytes + 4) / 1024.0) / f_plain
     write_scale = (rows * row_bytes / 1024.0) / w_plain
     # timed-region launches only: the largest grids are the full launch sets
